@@ -1,0 +1,181 @@
+#!/usr/bin/env python3
+"""Benchmark of the BRACE aggregation hot path on one MI355X.
+
+One step = one pass of the whole path (sign quantisation, share-reduce vote, consensus
+threshold, gather into the global update) over one synthetic batch of n client updates
+already resident in HBM.  Prints ONE JSON line on stdout; progress goes to stderr.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] [--no-cpu-baseline]
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published peak
+
+# HBM bytes per launch read from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (KiB per
+# dispatch, scaled by the same counters' reading for a copy kernel of known size).
+# Filled from the summaries kept under profiles/; None = not measured for that workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def pick_workload(name: str):
+    from paper_2501_17392_amd import synth
+    for w in synth.WORKLOADS:
+        if w.name == name or w.name.startswith(name + "_") or w.name.split("_")[0] == name:
+            return w
+    raise SystemExit(f"unknown workload {name!r}; choose from {[w.name for w in synth.WORKLOADS]}")
+
+
+def cpu_baseline(upd, w, lam, gpu_out, sample_cols):
+    """Time the plain-C oracle on the host cores over the first `sample_cols` columns of the
+    same input bytes, and check the GPU result against it on those columns."""
+    import numpy as np
+    from oracle import c_oracle
+
+    c_oracle.load()
+    k1 = min(w.d, sample_cols)
+    t0 = time.perf_counter()
+    host = upd[:, :k1].contiguous().cpu().numpy()
+    t_copy = time.perf_counter() - t0
+    threads = c_oracle.threads(0)
+    t0 = time.perf_counter()
+    want, _, _ = c_oracle.brace_direct(host, lam, 0, want_sums=False, want_bits=False, nthreads=0)
+    t_all = time.perf_counter() - t0
+    k1_single = max(1, k1 // 8)
+    t0 = time.perf_counter()
+    c_oracle.brace_direct(host[:, :k1_single], lam, 0, want_sums=False, want_bits=False, nthreads=1)
+    t_one = time.perf_counter() - t0
+    match = bool(np.array_equal(gpu_out[:k1].cpu().numpy(), want))
+    return {
+        "value": k1 / t_all,
+        "unit": "coords/s",
+        "cores": threads,
+        "kind": "oracle",
+        "sample": f"first {k1} of {w.d} coordinates x all {w.n} clients of the same input "
+                  f"({4 * w.n * k1 / 1e9:.2f} GB), plain-C definition loop with OpenMP over "
+                  f"coordinates; D2H copy ({t_copy:.1f} s) excluded",
+        "seconds": t_all,
+        "value_1thread": k1_single / t_one,
+        "gpu_matches_oracle_on_sample": match,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--lam", type=float, default=5.0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-cols", type=int, default=8_000_000)
+    ap.add_argument("--tuning", default="",
+                    help="vec,cols,unroll,nontemporal,xcd_swizzle (default: library defaults)")
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        raise SystemExit("bench.py: this build runs on ONE GPU only (no collectives, no second "
+                         "device); run with --gpus 1")
+
+    import torch
+    from paper_2501_17392_amd import binding as B
+    from paper_2501_17392_amd import synth
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs the MI355X (torch.cuda.is_available() is False)")
+    B.lib()                                   # fail loudly if the HIP library is not built
+    if args.tuning:
+        B.brace_set_tuning(*[int(x) for x in args.tuning.split(",")])
+    dev = "cuda:0"
+    w = pick_workload(args.workload)
+    log(f"[bench] workload {w.name}: n={w.n} f={w.f} d={w.d} ({w.input_bytes / 1e9:.2f} GB), "
+        f"lambda={args.lam}, tuning={B.brace_get_tuning()}")
+
+    t0 = time.perf_counter()
+    upd = synth.generate(w, dev)
+    torch.cuda.synchronize()
+    log(f"[bench] generated inputs in {time.perf_counter() - t0:.1f} s")
+    out = torch.empty(w.d, device=dev, dtype=torch.float32)
+    stream = torch.cuda.current_stream()
+
+    for _ in range(args.warmup):
+        B.brace_aggregate(upd, w.f, args.lam, out=out, stream=stream)
+    torch.cuda.synchronize()
+
+    K = args.steps
+    events = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        events[i].record(stream)
+        B.brace_aggregate(upd, w.f, args.lam, out=out, stream=stream)
+    events[K].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    per_launch_ms = sorted(events[i].elapsed_time(events[i + 1]) for i in range(K))
+    avg_ms = events[0].elapsed_time(events[K]) / K
+    ms_per_step = wall * 1e3 / K
+    algo_bytes = 4 * w.n * w.d + 4 * w.d          # read n*d fp32 once, write d fp32
+    achieved = algo_bytes / (avg_ms * 1e-3) / 1e9
+    log(f"[bench] {K} steps: wall {ms_per_step:.3f} ms/step, kernel avg {avg_ms:.3f} ms "
+        f"(min {per_launch_ms[0]:.3f}, median {per_launch_ms[K // 2]:.3f}) -> {achieved:.0f} GB/s "
+        f"= {achieved / HBM_PEAK_GBS:.1%} of {HBM_PEAK_GBS:.0f} GB/s")
+
+    result = {
+        "metric": "aggregated coordinates/sec (BRACE robust chunk aggregation)",
+        "value": w.d / (ms_per_step * 1e-3),
+        "unit": "coords/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": w.name, "n": w.n, "f": w.f, "d": w.d, "lambda": args.lam,
+            "input_bytes": w.input_bytes, "client_coords_per_s": w.n * w.d / (ms_per_step * 1e-3),
+            "launch": B.brace_get_tuning(), "input_checksum": synth.checksum(upd[:, : min(w.d, 1 << 20)]),
+        },
+        "roofline": {
+            "bound": "hbm",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
+            "kernel": "brace_vote_kernel",
+            "algorithmic_bytes_per_launch": algo_bytes,
+            "kernel_ms_avg": avg_ms,
+            "kernel_ms_min": per_launch_ms[0],
+            "kernel_ms_median": per_launch_ms[K // 2],
+        },
+    }
+    if not args.no_cpu_baseline:
+        log("[bench] timing the CPU oracle on a sample ...")
+        result["cpu_baseline"] = cpu_baseline(upd, w, args.lam, out, args.cpu_sample_cols)
+        log(f"[bench] oracle: {result['cpu_baseline']['value']:.3e} coords/s on "
+            f"{result['cpu_baseline']['cores']} threads; GPU matches oracle on the sample: "
+            f"{result['cpu_baseline']['gpu_matches_oracle_on_sample']}")
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

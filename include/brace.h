@@ -1,0 +1,129 @@
+/*
+ * brace.h -- C ABI of the MI355X (gfx950) BRACE robust chunk aggregation library.
+ *
+ * BRACE (Byzantine-robust ring-all-reduce) replaces the summation inside
+ * ring-all-reduce by a per-coordinate vote: every client quantises its update
+ * to its element-wise sign (Sec. 3, Phase I), the ring adds the signs chunk by
+ * chunk (Phase II, Share-Reduce), the owner of each chunk maps the sign-sum S
+ * to +1 if S > lambda and to -1 otherwise (Phase III, Eq. (1); App. A writes
+ * the same map as 2*I(S > lambda) - 1), and the +-1 chunks are circulated until
+ * every client holds the same full vector (Phase IV, Share-Only).
+ *
+ * Here all n clients' flattened updates are resident on one GPU.  The ring is
+ * chunk ownership and indexing: the gradient is split in n roughly equal
+ * sub-vectors (Sec. 2.2), each chunk is aggregated across the n clients'
+ * copies, and the aggregated chunks are written back ("gathered") at their
+ * place in the global update.
+ *
+ * Conventions
+ *   - Pointers named *_dev are DEVICE pointers; the caller owns every buffer.
+ *     The library allocates nothing and keeps no state besides the last error
+ *     text (thread-local) and the optional launch tuning (process-wide).
+ *   - Calls validate on the host, enqueue on `hip_stream` (a hipStream_t passed
+ *     as void*; NULL is the default stream) and return without synchronising.
+ *     BRACE_OK therefore means "validated and enqueued".
+ *   - Errors are return codes; nothing is thrown across this boundary.
+ *     brace_last_error() gives a short text for the last failure on this thread.
+ *   - Coordinates, chunks and clients are 0-indexed.
+ */
+#ifndef BRACE_H
+#define BRACE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum brace_status {
+    BRACE_OK = 0,
+    BRACE_EINVAL = 1,   /* NULL/invalid argument, bad struct_size, bad alignment        */
+    BRACE_ERANGE = 2,   /* chunk outside [0, n), n above BRACE_MAX_CLIENTS             */
+    BRACE_EHIP = 3      /* a HIP runtime call failed (text in brace_last_error)         */
+} brace_status_t;
+
+#define BRACE_MAX_CLIENTS 32767   /* sign-sums are delivered as int16 */
+
+/*
+ * Parameters of the consensus map (Sec. 3 Phase III, Eq. (1)) and optional outputs.
+ * Fill with brace_params_init() and then change what you need.
+ */
+typedef struct brace_params {
+    uint32_t struct_size;  /* sizeof(brace_params_t); checked                                    */
+    float    lambda;       /* threshold of Eq. (1); any finite real.  Sec. 5.1 uses 5.            */
+    int32_t  zero_sign;    /* vote cast by +0, -0 and NaN: 0 (default), +1 or -1.  The paper does  */
+                           /* not define sign(0); infinities and denormals keep their sign.       */
+    int32_t  reserved0;    /* must be 0                                                           */
+    int64_t  ld;           /* row pitch of updates_dev in elements; 0 means ld = d                 */
+    void*    out_bits_dev; /* optional 1-bit-per-dimension result (the Share-Only wire format of   */
+                           /* Sec. 3): bit j of byte b is coordinate 8b+j, 1 <=> +1.  Must be      */
+                           /* 4-byte aligned and hold 4*ceil(d/32) bytes; bits past d are zeroed.  */
+    int16_t* sums_dev;     /* optional sign-sums S[k] (end state of Share-Reduce), d entries       */
+} brace_params_t;
+
+/* struct_size, lambda = 5, zero_sign = 0, ld = 0, no optional outputs. */
+void brace_params_init(brace_params_t* params);
+
+/*
+ * Aggregate the whole update: Eq. (1) on every coordinate of every ring chunk,
+ * gathered into out_dev[0 .. d).
+ *
+ *   updates_dev  n rows of d fp32 values, row i (client i) at updates_dev + i*ld; read once.
+ *   n            number of clients, 1 .. BRACE_MAX_CLIENTS
+ *   d            dimension, >= 0 (0 is a no-op); d < n is allowed (some chunks are empty)
+ *   f            number of Byzantine clients the caller assumes, 0 <= f <= n.  Validated only:
+ *                Eq. (1) does not depend on it.
+ *   out_dev      d fp32 values, each exactly +1.0f or -1.0f.  May be NULL when out_bits_dev or
+ *                sums_dev is given.  Must not overlap updates_dev.
+ */
+int brace_aggregate(const float* updates_dev, int64_t n, int64_t d, int64_t f,
+                    const brace_params_t* params, float* out_dev, void* hip_stream);
+
+/*
+ * Aggregate one ring chunk c in [0, n): writes out_dev[lo_c .. hi_c) only (and the matching
+ * part of the optional outputs).  out_dev, out_bits_dev and sums_dev still address the FULL
+ * length-d vectors, so calling this for every chunk reproduces brace_aggregate byte for byte.
+ * Calls for different chunks may run concurrently on different streams (bits that share a
+ * 32-bit word with a neighbouring chunk are merged atomically).
+ */
+int brace_aggregate_chunk(const float* updates_dev, int64_t n, int64_t d, int64_t f,
+                          int64_t chunk, const brace_params_t* params, float* out_dev,
+                          void* hip_stream);
+
+/*
+ * Chunk partition (Sec. 2.2: "n roughly equal-sized sub-vectors").  Contiguous, ascending;
+ * with q = d div n, r = d mod n the first r chunks have q+1 coordinates, the rest q.
+ * Host arithmetic only.  [lo, hi) is half-open.
+ */
+int brace_chunk_range(int64_t n, int64_t d, int64_t chunk, int64_t* lo, int64_t* hi);
+
+/*
+ * Client that holds the fully reduced chunk after Share-Reduce in the simulated ring
+ * (client i sends to client i+1; the three-client example of Sec. 2.2 puts the second
+ * sub-vector on Client 1): owner = (chunk - 1) mod n.  Host arithmetic only.
+ */
+int brace_chunk_owner(int64_t n, int64_t chunk, int64_t* owner_client);
+
+/* Text of the last error on the calling thread ("" if none).  Static storage; do not free. */
+const char* brace_last_error(void);
+
+/*
+ * Launch tuning for the streaming kernel (process-wide, not thread-safe; meant for
+ * benchmarks and autotuning).  Every combination produces identical results.
+ */
+typedef struct brace_tuning {
+    uint32_t struct_size;  /* sizeof(brace_tuning_t)                                             */
+    int32_t  vec;          /* widest load in dwords: 0 = auto (what alignment allows), 1, 2, 4    */
+    int32_t  cols;         /* loads per lane per row: 1, 2 or 4                                   */
+    int32_t  unroll;       /* rows issued before the first is consumed: 2, 4, 8 or 16             */
+    int32_t  nontemporal;  /* 1: streaming (non-temporal) loads                                   */
+    int32_t  xcd_swizzle;  /* 1: give each of the 8 XCDs a contiguous span of the coordinates     */
+} brace_tuning_t;
+
+int brace_set_tuning(const brace_tuning_t* tuning);   /* NULL restores the defaults */
+int brace_get_tuning(brace_tuning_t* tuning);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BRACE_H */

@@ -1,0 +1,182 @@
+"""Thin ctypes binding of libbrace.so: argument marshalling only.
+
+Every step of the aggregation runs inside the HIP library.  Tensors are used
+for their device pointer, shape and pitch; PyTorch supplies device memory and
+the stream, nothing else.  If the library has not been built this module
+raises -- there is no fallback path.
+"""
+
+from __future__ import annotations
+
+import ctypes
+import os
+
+PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(PKG, "libbrace.so")
+
+BRACE_OK, BRACE_EINVAL, BRACE_ERANGE, BRACE_EHIP = 0, 1, 2, 3
+BRACE_MAX_CLIENTS = 32767
+
+
+class BraceParams(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", ctypes.c_uint32),
+        ("lambda_", ctypes.c_float),
+        ("zero_sign", ctypes.c_int32),
+        ("reserved0", ctypes.c_int32),
+        ("ld", ctypes.c_int64),
+        ("out_bits_dev", ctypes.c_void_p),
+        ("sums_dev", ctypes.c_void_p),
+    ]
+
+
+class BraceTuning(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", ctypes.c_uint32),
+        ("vec", ctypes.c_int32),
+        ("cols", ctypes.c_int32),
+        ("unroll", ctypes.c_int32),
+        ("nontemporal", ctypes.c_int32),
+        ("xcd_swizzle", ctypes.c_int32),
+    ]
+
+
+class BraceError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"brace status {code}: {text}")
+        self.code = code
+        self.text = text
+
+
+_lib = None
+
+EXPORTS = (
+    "brace_params_init", "brace_aggregate", "brace_aggregate_chunk", "brace_chunk_range",
+    "brace_chunk_owner", "brace_last_error", "brace_set_tuning", "brace_get_tuning",
+)
+
+
+def lib():
+    """The loaded shared library (raises if it has not been built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2501_17392_amd.build` "
+            "(there is no non-HIP fallback)")
+    L = ctypes.CDLL(LIB_PATH)
+    i64, vp = ctypes.c_int64, ctypes.c_void_p
+    pp = ctypes.POINTER(BraceParams)
+    L.brace_params_init.argtypes = [pp]
+    L.brace_params_init.restype = None
+    L.brace_aggregate.argtypes = [vp, i64, i64, i64, pp, vp, vp]
+    L.brace_aggregate.restype = ctypes.c_int
+    L.brace_aggregate_chunk.argtypes = [vp, i64, i64, i64, i64, pp, vp, vp]
+    L.brace_aggregate_chunk.restype = ctypes.c_int
+    L.brace_chunk_range.argtypes = [i64, i64, i64, ctypes.POINTER(i64), ctypes.POINTER(i64)]
+    L.brace_chunk_range.restype = ctypes.c_int
+    L.brace_chunk_owner.argtypes = [i64, i64, ctypes.POINTER(i64)]
+    L.brace_chunk_owner.restype = ctypes.c_int
+    L.brace_last_error.argtypes = []
+    L.brace_last_error.restype = ctypes.c_char_p
+    L.brace_set_tuning.argtypes = [ctypes.POINTER(BraceTuning)]
+    L.brace_set_tuning.restype = ctypes.c_int
+    L.brace_get_tuning.argtypes = [ctypes.POINTER(BraceTuning)]
+    L.brace_get_tuning.restype = ctypes.c_int
+    _lib = L
+    return L
+
+
+def brace_last_error() -> str:
+    return lib().brace_last_error().decode()
+
+
+def _check(rc: int):
+    if rc != BRACE_OK:
+        raise BraceError(rc, brace_last_error())
+
+
+def make_params(lam: float = 5.0, zero_sign: int = 0, ld: int = 0,
+                out_bits_ptr: int | None = None, sums_ptr: int | None = None) -> BraceParams:
+    p = BraceParams()
+    lib().brace_params_init(ctypes.byref(p))
+    p.lambda_ = float(lam)
+    p.zero_sign = int(zero_sign)
+    p.ld = int(ld)
+    p.out_bits_dev = out_bits_ptr
+    p.sums_dev = sums_ptr
+    return p
+
+
+def brace_chunk_range(n: int, d: int, chunk: int) -> tuple[int, int]:
+    lo, hi = ctypes.c_int64(), ctypes.c_int64()
+    _check(lib().brace_chunk_range(n, d, chunk, ctypes.byref(lo), ctypes.byref(hi)))
+    return lo.value, hi.value
+
+
+def brace_chunk_owner(n: int, chunk: int) -> int:
+    o = ctypes.c_int64()
+    _check(lib().brace_chunk_owner(n, chunk, ctypes.byref(o)))
+    return o.value
+
+
+def _stream_handle(stream) -> int | None:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if hasattr(stream, "cuda_stream"):
+        return stream.cuda_stream
+    return int(stream)
+
+
+def _ptr(t) -> int | None:
+    return None if t is None else t.data_ptr()
+
+
+def _matrix(updates):
+    if updates.dim() != 2 or updates.stride(1) != 1 and updates.shape[1] > 1:
+        raise ValueError("updates must be (n, d) with unit column stride")
+    n, d = updates.shape
+    ld = updates.stride(0) if n > 1 else max(d, 1)
+    return n, d, ld
+
+
+def brace_aggregate(updates, f: int, lam: float = 5.0, zero_sign: int = 0, out=None,
+                    out_bits=None, sums=None, stream=None):
+    """brace_aggregate of the C ABI on device tensors; returns `out`.
+
+    updates: (n, d) float32 device tensor, unit column stride, any row pitch >= d.
+    out: float32[d], out_bits: int32/uint8 storage of 4*ceil(d/32) bytes, sums: int16[d].
+    """
+    n, d, ld = _matrix(updates)
+    p = make_params(lam, zero_sign, ld, _ptr(out_bits), _ptr(sums))
+    _check(lib().brace_aggregate(updates.data_ptr(), n, d, f, ctypes.byref(p), _ptr(out),
+                                 _stream_handle(stream)))
+    return out
+
+
+def brace_aggregate_chunk(updates, f: int, chunk: int, lam: float = 5.0, zero_sign: int = 0,
+                          out=None, out_bits=None, sums=None, stream=None):
+    """brace_aggregate_chunk of the C ABI; `out` etc. are the FULL length-d vectors."""
+    n, d, ld = _matrix(updates)
+    p = make_params(lam, zero_sign, ld, _ptr(out_bits), _ptr(sums))
+    _check(lib().brace_aggregate_chunk(updates.data_ptr(), n, d, f, chunk, ctypes.byref(p),
+                                       _ptr(out), _stream_handle(stream)))
+    return out
+
+
+def brace_set_tuning(vec: int = 0, cols: int = 2, unroll: int = 8, nontemporal: int = 1,
+                     xcd_swizzle: int = 0):
+    t = BraceTuning(ctypes.sizeof(BraceTuning), vec, cols, unroll, nontemporal, xcd_swizzle)
+    _check(lib().brace_set_tuning(ctypes.byref(t)))
+
+
+def brace_reset_tuning():
+    _check(lib().brace_set_tuning(None))
+
+
+def brace_get_tuning() -> dict:
+    t = BraceTuning()
+    _check(lib().brace_get_tuning(ctypes.byref(t)))
+    return {k: getattr(t, k) for k, _ in BraceTuning._fields_ if k != "struct_size"}

@@ -1,0 +1,160 @@
+"""The C ABI without a GPU: the library loads, exports what the header declares, and the
+host-side arithmetic and argument validation behave as documented.  No kernel is launched:
+every call here either is pure host arithmetic or is rejected before any HIP call."""
+
+import ctypes
+import os
+import re
+
+import pytest
+
+from oracle import brace_oracle as O
+from paper_2501_17392_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+FAKE_IN = 0x7F00_0000_0000     # never dereferenced: validation fails first
+FAKE_OUT = 0x7F80_0000_0000
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2501_17392_amd.build import build_library
+        build_library()
+    return B.lib()
+
+
+def _declared_functions():
+    names = []
+    inc = os.path.join(ROOT, "include")
+    for fn in sorted(os.listdir(inc)):
+        if fn.endswith(".h"):
+            text = open(os.path.join(inc, fn)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names += re.findall(r"\b([a-z][a-z0-9_]*)\s*\([^;{]*\)\s*;", text)
+    return sorted(set(names))
+
+
+def test_library_exports_every_declared_symbol(L):
+    declared = _declared_functions()
+    assert "brace_aggregate" in declared and "brace_aggregate_chunk" in declared
+    for name in declared:
+        assert hasattr(L, name), f"{name} declared in include/ but not exported"
+    assert set(B.EXPORTS) <= set(declared)
+
+
+def test_struct_layouts_match_the_header():
+    assert ctypes.sizeof(B.BraceParams) == 40
+    assert B.BraceParams.ld.offset == 16
+    assert B.BraceParams.out_bits_dev.offset == 24
+    assert B.BraceParams.sums_dev.offset == 32
+    assert ctypes.sizeof(B.BraceTuning) == 24
+
+
+def test_params_init_defaults(L):
+    p = B.make_params()
+    assert p.struct_size == ctypes.sizeof(B.BraceParams)
+    assert p.lambda_ == 5.0 and p.zero_sign == 0 and p.ld == 0
+    assert p.out_bits_dev is None and p.sums_dev is None
+
+
+@pytest.mark.parametrize("n,d", [(1, 0), (1, 7), (3, 3), (10, 10_000), (20, 1_000_003),
+                                 (50, 11_173_962), (100, 25_000_000), (64, 100_000_000), (7, 3)])
+def test_chunk_range_and_owner_match_the_oracle(L, n, d):
+    for c in sorted({0, 1 % n, n // 2, n - 1}):
+        assert B.brace_chunk_range(n, d, c) == O.chunk_range(n, d, c)
+        assert B.brace_chunk_owner(n, c) == O.chunk_owner(n, c)
+
+
+def test_chunk_helpers_reject_bad_arguments(L):
+    lo, hi = ctypes.c_int64(), ctypes.c_int64()
+    assert L.brace_chunk_range(0, 5, 0, ctypes.byref(lo), ctypes.byref(hi)) == B.BRACE_EINVAL
+    assert L.brace_chunk_range(3, -1, 0, ctypes.byref(lo), ctypes.byref(hi)) == B.BRACE_EINVAL
+    assert L.brace_chunk_range(3, 5, 3, ctypes.byref(lo), ctypes.byref(hi)) == B.BRACE_ERANGE
+    assert L.brace_chunk_range(3, 5, -1, ctypes.byref(lo), ctypes.byref(hi)) == B.BRACE_ERANGE
+    assert L.brace_chunk_range(3, 5, 0, None, ctypes.byref(hi)) == B.BRACE_EINVAL
+    assert "chunk" in B.brace_last_error() or "NULL" in B.brace_last_error()
+    o = ctypes.c_int64()
+    assert L.brace_chunk_owner(3, 3, ctypes.byref(o)) == B.BRACE_ERANGE
+    assert L.brace_chunk_owner(0, 0, ctypes.byref(o)) == B.BRACE_EINVAL
+    assert L.brace_chunk_owner(3, 0, None) == B.BRACE_EINVAL
+    with pytest.raises(B.BraceError) as ei:
+        B.brace_chunk_range(3, 5, 9)
+    assert ei.value.code == B.BRACE_ERANGE
+
+
+def _agg(L, *, inp=FAKE_IN, n=4, d=100, f=1, p="default", out=FAKE_OUT, chunk=None, **kw):
+    if p == "default":
+        p = B.make_params(**kw)
+    pref = ctypes.byref(p) if p is not None else None
+    if chunk is None:
+        return L.brace_aggregate(inp, n, d, f, pref, out, None)
+    return L.brace_aggregate_chunk(inp, n, d, f, chunk, pref, out, None)
+
+
+def test_aggregate_rejects_invalid_arguments_before_touching_the_gpu(L):
+    E, R = B.BRACE_EINVAL, B.BRACE_ERANGE
+    assert _agg(L, p=None) == E
+    assert _agg(L, inp=None) == E
+    assert _agg(L, out=None) == E                       # no output at all
+    assert _agg(L, n=0) == E
+    assert _agg(L, n=-3) == E
+    assert _agg(L, n=B.BRACE_MAX_CLIENTS + 1, f=0) == R
+    assert _agg(L, d=-1) == E
+    assert _agg(L, f=-1) == E
+    assert _agg(L, f=5) == E                            # f > n
+    assert _agg(L, lam=float("nan")) == E
+    assert _agg(L, lam=float("inf")) == E
+    assert _agg(L, zero_sign=2) == E
+    assert _agg(L, zero_sign=-2) == E
+    assert _agg(L, ld=99) == E                          # pitch smaller than d
+    assert _agg(L, inp=FAKE_IN + 2) == E                # misaligned
+    assert _agg(L, out=FAKE_OUT + 1) == E
+    assert _agg(L, out_bits_ptr=FAKE_OUT + 0x1002) == E
+    assert _agg(L, sums_ptr=FAKE_OUT + 0x2001) == E
+    assert _agg(L, out=FAKE_IN + 4 * 150) == E          # out inside the input matrix
+    bad = B.make_params()
+    bad.struct_size = 12
+    assert _agg(L, p=bad) == E
+    assert "struct_size" in B.brace_last_error()
+    bad = B.make_params()
+    bad.reserved0 = 1
+    assert _agg(L, p=bad) == E
+    assert _agg(L, chunk=4) == R
+    assert _agg(L, chunk=-1) == R
+    assert "chunk" in B.brace_last_error()
+
+
+def test_degenerate_sizes_are_accepted_without_a_launch(L):
+    assert _agg(L, d=0) == B.BRACE_OK                   # nothing to do
+    assert _agg(L, n=7, d=3, f=0, chunk=5) == B.BRACE_OK  # d < n: chunk 5 is empty
+    assert _agg(L, n=4, d=0, f=4) == B.BRACE_OK         # f = n is allowed; the rule ignores f
+
+
+def test_tuning_roundtrip_and_validation(L):
+    B.brace_reset_tuning()
+    base = B.brace_get_tuning()
+    assert base == {"vec": 0, "cols": 2, "unroll": 8, "nontemporal": 1, "xcd_swizzle": 0}
+    B.brace_set_tuning(vec=2, cols=4, unroll=16, nontemporal=0, xcd_swizzle=1)
+    assert B.brace_get_tuning() == {"vec": 2, "cols": 4, "unroll": 16, "nontemporal": 0,
+                                    "xcd_swizzle": 1}
+    with pytest.raises(B.BraceError):
+        B.brace_set_tuning(vec=3)
+    with pytest.raises(B.BraceError):
+        B.brace_set_tuning(cols=3)
+    with pytest.raises(B.BraceError):
+        B.brace_set_tuning(unroll=5)
+    B.brace_reset_tuning()
+    assert B.brace_get_tuning() == base
+
+
+def test_binding_has_no_fallback_path():
+    # The product path must not reach the oracle or any CPU implementation.
+    pkg = os.path.join(ROOT, "paper_2501_17392_amd")
+    for fn in os.listdir(pkg):
+        if fn.endswith(".py"):
+            text = open(os.path.join(pkg, fn)).read()
+            assert "import oracle" not in text and "from oracle" not in text, fn
+    text = open(os.path.join(ROOT, "oracle", "brace_oracle.py")).read()
+    assert "paper_2501_17392_amd" not in text
