@@ -82,7 +82,7 @@ def main():
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--lam", type=float, default=5.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-cols", type=int, default=8_000_000)
+    ap.add_argument("--cpu-sample-cols", type=int, default=25_000_000)
     ap.add_argument("--tuning", default="",
                     help="vec,cols,unroll,nontemporal,xcd_swizzle (default: library defaults)")
     args = ap.parse_args()

@@ -70,7 +70,8 @@ void brace_params_init(brace_params_t* params);
  *
  *   updates_dev  n rows of d fp32 values, row i (client i) at updates_dev + i*ld; read once.
  *   n            number of clients, 1 .. BRACE_MAX_CLIENTS
- *   d            dimension, >= 0 (0 is a no-op); d < n is allowed (some chunks are empty)
+ *   d            dimension, >= 0; d < n is allowed (some chunks are empty).  d = 0 is a no-op
+ *                that touches no buffer (pointers may then be NULL).
  *   f            number of Byzantine clients the caller assumes, 0 <= f <= n.  Validated only:
  *                Eq. (1) does not depend on it.
  *   out_dev      d fp32 values, each exactly +1.0f or -1.0f.  May be NULL when out_bits_dev or

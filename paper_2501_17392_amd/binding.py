@@ -65,6 +65,12 @@ def lib():
         raise ImportError(
             f"{LIB_PATH} is missing: build it with `python -m paper_2501_17392_amd.build` "
             "(there is no non-HIP fallback)")
+    # One process must hold ONE HIP runtime.  PyTorch ships its own libamdhip64 (same
+    # soname as the system one); importing torch first makes the dynamic loader bind
+    # libbrace.so to that already-loaded runtime, so device pointers and streams handed
+    # over from torch are valid in the library.  Loaded the other way round, the process
+    # ends up with two runtimes and the second one sees no device.
+    import torch  # noqa: F401
     L = ctypes.CDLL(LIB_PATH)
     i64, vp = ctypes.c_int64, ctypes.c_void_p
     pp = ctypes.POINTER(BraceParams)

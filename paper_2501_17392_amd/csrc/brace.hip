@@ -348,6 +348,10 @@ int validate(const float* updates, int64_t n, int64_t d, int64_t f, const brace_
     if (p->ld != 0 && p->ld < d)
         return fail(BRACE_EINVAL, "ld = %lld is smaller than d = %lld", (long long)p->ld,
                     (long long)d);
+    *ld_out = p->ld ? p->ld : d;
+    *thresh_out = 0;
+    if (d == 0)
+        return BRACE_OK;       // nothing is read or written, so empty buffers may be NULL
     if (!updates)
         return fail(BRACE_EINVAL, "updates_dev is NULL");
     if (!out && !p->out_bits_dev && !p->sums_dev)

@@ -128,6 +128,8 @@ def test_aggregate_rejects_invalid_arguments_before_touching_the_gpu(L):
 
 def test_degenerate_sizes_are_accepted_without_a_launch(L):
     assert _agg(L, d=0) == B.BRACE_OK                   # nothing to do
+    assert _agg(L, d=0, inp=None, out=None) == B.BRACE_OK  # empty buffers may be NULL
+    assert _agg(L, d=0, lam=float("nan")) == B.BRACE_EINVAL  # scalars are still checked
     assert _agg(L, n=7, d=3, f=0, chunk=5) == B.BRACE_OK  # d < n: chunk 5 is empty
     assert _agg(L, n=4, d=0, f=4) == B.BRACE_OK         # f = n is allowed; the rule ignores f
 
