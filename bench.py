@@ -83,6 +83,9 @@ def main():
     ap.add_argument("--lam", type=float, default=5.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-cols", type=int, default=25_000_000)
+    ap.add_argument("--probe", action="store_true",
+                    help="also run the plain read / copy kernels on 1 GiB (counter calibration "
+                         "and linear-access bandwidth); reported under 'probe'")
     ap.add_argument("--tuning", default="",
                     help="vec,cols,unroll,nontemporal,xcd_swizzle (default: library defaults)")
     args = ap.parse_args()
@@ -161,13 +164,33 @@ def main():
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
             "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
-            "kernel": "brace_vote_kernel",
+            "kernel": "brace_vote_kernel (+ brace_expand_kernel, the write-only second phase)",
             "algorithmic_bytes_per_launch": algo_bytes,
             "kernel_ms_avg": avg_ms,
             "kernel_ms_min": per_launch_ms[0],
             "kernel_ms_median": per_launch_ms[K // 2],
         },
     }
+    if args.probe:
+        nel = (1 << 30) // 4
+        src = torch.randn(nel, device=dev)
+        dst = torch.empty_like(src)
+        sink = torch.zeros(4, device=dev)
+        probe = {"bytes": nel * 4}
+        for name, fn, moved in (("read", lambda: B.brace_probe_read(src, sink, 1, stream), nel * 4),
+                                ("copy", lambda: B.brace_probe_copy(dst, src, stream), 2 * nel * 4)):
+            for _ in range(2):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(10):
+                fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            probe[name + "_GBps"] = moved / (e0.elapsed_time(e1) / 10 * 1e-3) / 1e9
+        result["probe"] = probe
+        log(f"[bench] probe: {probe}")
+        del src, dst
     if not args.no_cpu_baseline:
         log("[bench] timing the CPU oracle on a sample ...")
         result["cpu_baseline"] = cpu_baseline(upd, w, args.lam, out, args.cpu_sample_cols)

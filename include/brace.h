@@ -115,14 +115,30 @@ const char* brace_last_error(void);
 typedef struct brace_tuning {
     uint32_t struct_size;  /* sizeof(brace_tuning_t)                                             */
     int32_t  vec;          /* widest load in dwords: 0 = auto (what alignment allows), 1, 2, 4    */
-    int32_t  cols;         /* loads per lane per row: 1, 2 or 4                                   */
-    int32_t  unroll;       /* rows issued before the first is consumed: 2, 4, 8 or 16             */
+    int32_t  cols;         /* loads per lane per row: 1, 2, 4 or 8                                */
+    int32_t  unroll;       /* rows issued before the first is consumed: 2, 4 or 8                 */
     int32_t  nontemporal;  /* 1: streaming (non-temporal) loads                                   */
     int32_t  xcd_swizzle;  /* 1: give each of the 8 XCDs a contiguous span of the coordinates     */
+    int32_t  persist;      /* 0: one tile per block; k > 0: at most k blocks per compute unit,    */
+                           /* each walking several tiles (all resident waves share one panel)     */
+    int32_t  pipeline;     /* 1: request the next batch of rows before consuming the current one  */
+    int32_t  split_writes; /* fp32 output written by a second, write-only kernel from the bits:   */
+                           /* 0 = for large ranges (default), 1 = never, 2 = whenever possible    */
 } brace_tuning_t;
 
 int brace_set_tuning(const brace_tuning_t* tuning);   /* NULL restores the defaults */
 int brace_get_tuning(brace_tuning_t* tuning);
+
+/*
+ * Measurement aids (not part of the method): a streaming read and a plain copy of a buffer
+ * of known size, used to calibrate the HBM byte counters and to report the bandwidth a
+ * trivially linear access pattern reaches on the same device.  Buffers are device memory,
+ * 16-byte aligned, nbytes a multiple of 16.  sink_dev is 4 bytes that are (practically)
+ * never written.  Enqueued on hip_stream; no synchronisation.
+ */
+int brace_probe_read(const void* src_dev, int64_t nbytes, int32_t nontemporal, void* sink_dev,
+                     void* hip_stream);
+int brace_probe_copy(void* dst_dev, const void* src_dev, int64_t nbytes, void* hip_stream);
 
 #ifdef __cplusplus
 }

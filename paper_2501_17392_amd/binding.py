@@ -38,6 +38,9 @@ class BraceTuning(ctypes.Structure):
         ("unroll", ctypes.c_int32),
         ("nontemporal", ctypes.c_int32),
         ("xcd_swizzle", ctypes.c_int32),
+        ("persist", ctypes.c_int32),
+        ("pipeline", ctypes.c_int32),
+        ("split_writes", ctypes.c_int32),
     ]
 
 
@@ -53,6 +56,7 @@ _lib = None
 EXPORTS = (
     "brace_params_init", "brace_aggregate", "brace_aggregate_chunk", "brace_chunk_range",
     "brace_chunk_owner", "brace_last_error", "brace_set_tuning", "brace_get_tuning",
+    "brace_probe_read", "brace_probe_copy",
 )
 
 
@@ -90,6 +94,10 @@ def lib():
     L.brace_set_tuning.restype = ctypes.c_int
     L.brace_get_tuning.argtypes = [ctypes.POINTER(BraceTuning)]
     L.brace_get_tuning.restype = ctypes.c_int
+    L.brace_probe_read.argtypes = [vp, i64, ctypes.c_int32, vp, vp]
+    L.brace_probe_read.restype = ctypes.c_int
+    L.brace_probe_copy.argtypes = [vp, vp, i64, vp]
+    L.brace_probe_copy.restype = ctypes.c_int
     _lib = L
     return L
 
@@ -172,9 +180,11 @@ def brace_aggregate_chunk(updates, f: int, chunk: int, lam: float = 5.0, zero_si
     return out
 
 
-def brace_set_tuning(vec: int = 0, cols: int = 2, unroll: int = 8, nontemporal: int = 1,
-                     xcd_swizzle: int = 0):
-    t = BraceTuning(ctypes.sizeof(BraceTuning), vec, cols, unroll, nontemporal, xcd_swizzle)
+def brace_set_tuning(vec: int = 0, cols: int = 8, unroll: int = 2, nontemporal: int = 1,
+                     xcd_swizzle: int = 0, persist: int = 0, pipeline: int = 1,
+                     split_writes: int = 0):
+    t = BraceTuning(ctypes.sizeof(BraceTuning), vec, cols, unroll, nontemporal, xcd_swizzle,
+                    persist, pipeline, split_writes)
     _check(lib().brace_set_tuning(ctypes.byref(t)))
 
 
@@ -186,3 +196,16 @@ def brace_get_tuning() -> dict:
     t = BraceTuning()
     _check(lib().brace_get_tuning(ctypes.byref(t)))
     return {k: getattr(t, k) for k, _ in BraceTuning._fields_ if k != "struct_size"}
+
+
+def brace_probe_read(src, sink, nontemporal: int = 1, stream=None):
+    """Streaming read of a whole device tensor (measurement aid)."""
+    nbytes = src.numel() * src.element_size()
+    _check(lib().brace_probe_read(src.data_ptr(), nbytes, int(nontemporal), sink.data_ptr(),
+                                  _stream_handle(stream)))
+
+
+def brace_probe_copy(dst, src, stream=None):
+    """Plain copy of a whole device tensor (measurement aid)."""
+    nbytes = src.numel() * src.element_size()
+    _check(lib().brace_probe_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream_handle(stream)))

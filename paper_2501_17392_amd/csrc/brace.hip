@@ -1,26 +1,6 @@
-// BRACE robust chunk aggregation for MI355X (gfx950): kernels and C ABI.
-//
-// What is computed (Sec. 3, Phases I-IV; Eq. (1)): for every coordinate k of a
-// ring chunk, S[k] = sum over the n clients of sign(g_i[k]), and the result is
-// +1 if S[k] > lambda, else -1, written at k's place in the global update.
-//
-// Shape of the work: a pure stream.  The n x d fp32 matrix is read exactly once
-// (4*n bytes per coordinate) and 4 bytes per coordinate are written, so the
-// bound is HBM bandwidth.  There is no reuse, no contraction, no cross-lane
-// traffic in the main loop: each lane owns V consecutive coordinates per load
-// slot and keeps two small integer counters per coordinate (#positive,
-// #negative) in registers while it walks down the n client rows.
-//
-// Launch layout.  The range [lo, hi) of a call is split in
-//   body  [lo_a, hi_a): whole "wave slots" of 64*V coordinates, aligned to
-//         64*V coordinates from coordinate 0, handled with V-dword loads and
-//         no bounds checks;
-//   edges [lo, lo_a) and [hi_a, hi): at most 2*(64*V-1) coordinates, one
-//         thread per coordinate with dword loads, run by extra blocks at the
-//         end of the same grid.
-// A wave owns COLS adjacent slots, i.e. a contiguous run of 64*V*COLS floats
-// in every row; the row pointer is wave-uniform so row stepping is scalar
-// arithmetic and each load is "scalar base + lane offset".
+// BRACE robust chunk aggregation for MI355X (gfx950): C ABI, host logic, and the small
+// kernels (bit expansion, measurement aids).  The streaming vote kernel lives in
+// vote_kernel.hpp and is instantiated per load width in vote_v{1,2,4}.hip.
 
 #include <hip/hip_runtime.h>
 
@@ -31,12 +11,15 @@
 #include <cstring>
 
 #include "brace.h"
+#include "vote_kernel.hpp"
 
 namespace {
 
-constexpr int kBlock = 256;                 // 4 waves of 64
-constexpr int kWaves = kBlock / 64;
-constexpr int kXcds = 8;                    // MI355X: 8 XCDs, blocks are dealt round-robin
+using namespace brace_dev;
+
+// Ranges with fewer 1024-coordinate groups than this are written in one kernel: the second
+// launch would cost more than separating the writes from the read stream saves.
+constexpr int64_t kSplitMinGroups = 2048;
 
 thread_local char g_err[256] = "";
 
@@ -54,268 +37,114 @@ brace_tuning_t default_tuning()
     brace_tuning_t t;
     t.struct_size = sizeof(brace_tuning_t);
     t.vec = 0;
-    t.cols = 2;
-    t.unroll = 8;
+    t.cols = 8;
+    t.unroll = 2;
     t.nontemporal = 1;
     t.xcd_swizzle = 0;
+    t.persist = 0;
+    t.pipeline = 1;
+    t.split_writes = 0;
     return t;
+}
+
+// Compute units of the current device (0 if it cannot be queried); cached per process.
+int compute_units()
+{
+    static int cached = -1;
+    if (cached < 0) {
+        int dev = 0, cu = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
+            cached = cu;
+        else
+            cached = 0;
+    }
+    return cached;
 }
 
 brace_tuning_t g_tuning = default_tuning();
 
-template <int V> struct Vec;
-template <> struct Vec<1> { typedef float type; };
-template <> struct Vec<2> { typedef float type __attribute__((ext_vector_type(2))); };
-template <> struct Vec<4> { typedef float type __attribute__((ext_vector_type(4))); };
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-template <int V> struct IVec;
-template <> struct IVec<1> { typedef short type; };
-template <> struct IVec<2> { typedef short type __attribute__((ext_vector_type(2))); };
-template <> struct IVec<4> { typedef short type __attribute__((ext_vector_type(4))); };
-
-template <int V>
-__device__ __forceinline__ float elem(const typename Vec<V>::type& v, int e)
-{
-    if constexpr (V == 1) return v; else return v[e];
-}
-
-template <int V, bool NT>
-__device__ __forceinline__ typename Vec<V>::type load_vec(const float* p)
-{
-    typedef typename Vec<V>::type T;
-    if constexpr (NT)
-        return __builtin_nontemporal_load(reinterpret_cast<const T*>(p));
-    else
-        return *reinterpret_cast<const T*>(p);
-}
-
-// Scalars of one launch.  Pointers are separate kernel parameters so that the compiler
-// knows they are global memory and keeps wave-uniform address arithmetic in SGPRs.
-struct VoteArgs {
-    int64_t ld;             // row i at updates + i*ld
-    int32_t n;
-    int32_t thresh;         // result is +1 iff S >= thresh  (thresh = floor(lambda) + 1)
-    int32_t zero_sign;
-    int32_t swizzle;        // XCD-aware block -> tile map
-    int64_t lo, hi;         // coordinates of this call
-    int64_t lo_a, hi_a;     // aligned body
-    int64_t d;              // full dimension (bit padding past d is zeroed)
-    int64_t body_blocks;    // blocks that run the body; the rest run the edges
-};
-
-// Sign-sum from the two counters (Phase I + II); the consensus map (Phase III) is
-// "sum >= thresh".
-__device__ __forceinline__ int sign_sum(int pos, int neg, int n, int zero_sign)
-{
-    return pos - neg + zero_sign * (n - pos - neg);
-}
-
-// One wave: COLS adjacent slots starting at wave-uniform coordinate k0.
-template <int V, int COLS, int RU, bool NT>
-__device__ __forceinline__ void vote_slots(const float* __restrict__ updates,
-                                           float* __restrict__ out, uint32_t* __restrict__ bits,
-                                           int16_t* __restrict__ sums, int64_t ld, int n,
-                                           int thresh, int zero_sign, int64_t k0, int lane)
-{
-    typedef typename Vec<V>::type VT;
-    int pos[COLS][V], neg[COLS][V];
-#pragma unroll
-    for (int c = 0; c < COLS; ++c)
-#pragma unroll
-        for (int e = 0; e < V; ++e) { pos[c][e] = 0; neg[c][e] = 0; }
-
-    const float* row = updates + k0;            // wave-uniform
-    const uint32_t loff = (uint32_t)lane * V;   // per lane, in elements
-
-    int i = 0;
-    for (; i + RU <= n; i += RU) {
-        VT x[RU][COLS];
-#pragma unroll
-        for (int r = 0; r < RU; ++r)
-#pragma unroll
-            for (int c = 0; c < COLS; ++c)
-                x[r][c] = load_vec<V, NT>(row + (int64_t)r * ld + loff + c * (64 * V));
-        // keep all RU*COLS loads in flight before the first compare waits on one
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int r = 0; r < RU; ++r)
-#pragma unroll
-            for (int c = 0; c < COLS; ++c)
-#pragma unroll
-                for (int e = 0; e < V; ++e) {
-                    const float v = elem<V>(x[r][c], e);
-                    pos[c][e] += (v > 0.0f) ? 1 : 0;
-                    neg[c][e] += (v < 0.0f) ? 1 : 0;
-                }
-        row += (int64_t)RU * ld;
-    }
-    for (; i < n; ++i) {
-        VT x[COLS];
-#pragma unroll
-        for (int c = 0; c < COLS; ++c)
-            x[c] = load_vec<V, NT>(row + loff + c * (64 * V));
-#pragma unroll
-        for (int c = 0; c < COLS; ++c)
-#pragma unroll
-            for (int e = 0; e < V; ++e) {
-                const float v = elem<V>(x[c], e);
-                pos[c][e] += (v > 0.0f) ? 1 : 0;
-                neg[c][e] += (v < 0.0f) ? 1 : 0;
-            }
-        row += ld;
-    }
-
-#pragma unroll
-    for (int c = 0; c < COLS; ++c) {
-        const int64_t k = k0 + c * (64 * V) + loff;
-        int s[V];
-        uint32_t mybits = 0;
-#pragma unroll
-        for (int e = 0; e < V; ++e) {
-            s[e] = sign_sum(pos[c][e], neg[c][e], n, zero_sign);
-            mybits |= (s[e] >= thresh ? 1u : 0u) << e;
-        }
-        if (out) {
-            VT o;
-#pragma unroll
-            for (int e = 0; e < V; ++e) {
-                const float v = (s[e] >= thresh) ? 1.0f : -1.0f;
-                if constexpr (V == 1) o = v; else o[e] = v;
-            }
-            *reinterpret_cast<VT*>(out + k) = o;
-        }
-        if (sums) {
-            typename IVec<V>::type sv;
-#pragma unroll
-            for (int e = 0; e < V; ++e) {
-                if constexpr (V == 1) sv = (short)s[e]; else sv[e] = (short)s[e];
-            }
-            *reinterpret_cast<typename IVec<V>::type*>(sums + k) = sv;
-        }
-        if (bits) {
-            // 32/V lanes share one 32-bit word; OR them together, the first lane stores.
-            constexpr int L = 32 / V;
-            uint32_t w = mybits << (V * (lane & (L - 1)));
-#pragma unroll
-            for (int m = 1; m < L; m <<= 1)
-                w |= (uint32_t)__shfl_xor((int)w, m, 64);
-            if ((lane & (L - 1)) == 0)
-                bits[k >> 5] = w;
-        }
-    }
-}
-
-// Edge coordinates: one thread each, dword loads, bits merged atomically because a
-// 32-bit word can be shared with a neighbouring chunk's call.
-__device__ __forceinline__ void vote_edges(const float* __restrict__ updates,
-                                           float* __restrict__ out, uint32_t* __restrict__ bits,
-                                           int16_t* __restrict__ sums, const VoteArgs& a, int64_t e)
-{
-    const int64_t head = a.lo_a - a.lo;
-    const int64_t k = (e < head) ? a.lo + e : a.hi_a + (e - head);
-    int64_t hi_ext = a.hi;
-    if (bits && a.hi == a.d)
-        hi_ext = (a.d + 31) & ~(int64_t)31;      // zero the padding bits of the last word
-    if (k >= hi_ext)
-        return;
-    if (k >= a.hi) {
-        atomicAnd(&bits[k >> 5], ~(1u << (k & 31)));
-        return;
-    }
-    const float* p = updates + k;
-    int pos = 0, neg = 0;
-    for (int i = 0; i < a.n; ++i) {
-        const float v = *p;
-        pos += (v > 0.0f) ? 1 : 0;
-        neg += (v < 0.0f) ? 1 : 0;
-        p += a.ld;
-    }
-    const int s = sign_sum(pos, neg, a.n, a.zero_sign);
-    const bool up = s >= a.thresh;
-    if (out)
-        out[k] = up ? 1.0f : -1.0f;
-    if (sums)
-        sums[k] = (int16_t)s;
-    if (bits) {
-        if (up)
-            atomicOr(&bits[k >> 5], 1u << (k & 31));
-        else
-            atomicAnd(&bits[k >> 5], ~(1u << (k & 31)));
-    }
-}
-
-template <int V, int COLS, int RU, bool NT>
+// Second phase of a split call: one wave turns the 32 bit-words of a 1024-coordinate group
+// into 1024 floats.  `words` is the linear bit array, or null when the words were parked in
+// the first 128 bytes of the group's own 4 KiB of `out`; the wave reads all 32 words with one
+// load before its first store, so overwriting them is safe.
 __global__ void __launch_bounds__(kBlock)
-brace_vote_kernel(const float* __restrict__ updates, float* __restrict__ out,
-                  uint32_t* __restrict__ bits, int16_t* __restrict__ sums, const VoteArgs a)
+brace_expand_kernel(float* out, const uint32_t* words, int64_t lo_s, int64_t groups)
 {
-    const int64_t b = blockIdx.x;
-    if (b >= a.body_blocks) {
-        vote_edges(updates, out, bits, sums, a, (b - a.body_blocks) * kBlock + threadIdx.x);
-        return;
-    }
-    // Blocks are dealt to the 8 XCDs round-robin.  With the swizzle, XCD x works on the
-    // x-th eighth of the tiles, so neighbouring tiles (which share boundary cache lines
-    // when rows are not line-aligned) meet in the same L2.
-    int64_t tile = b;
-    if (a.swizzle) {
-        const int64_t per = a.body_blocks / kXcds;     // body_blocks is a multiple of 8 here
-        tile = (b % kXcds) * per + b / kXcds;
-    }
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    constexpr int64_t kSlot = 64 * V;
-    const int64_t slots = (a.hi_a - a.lo_a) / kSlot;
-    const int64_t s0 = (tile * kWaves + wave) * COLS;
-    if (s0 >= slots)
+    const int64_t g = (int64_t)blockIdx.x * kWaves + wave;
+    if (g >= groups)
         return;
-    const int64_t k0 = a.lo_a + s0 * kSlot;
-    if (s0 + COLS <= slots) {
-        vote_slots<V, COLS, RU, NT>(updates, out, bits, sums, a.ld, a.n, a.thresh, a.zero_sign,
-                                    k0, lane);
-    } else {
-        for (int64_t s = s0; s < slots; ++s)       // fewer than COLS slots left at the very end
-            vote_slots<V, 1, RU, NT>(updates, out, bits, sums, a.ld, a.n, a.thresh, a.zero_sign,
-                                     a.lo_a + s * kSlot, lane);
+    const int64_t k0 = lo_s + g * kGroup;
+    const uint32_t* src = words ? words + (k0 >> 5) : reinterpret_cast<const uint32_t*>(out) + k0;
+    const uint32_t w = src[lane & 31];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t ww = (uint32_t)__shfl((int)w, 8 * j + (lane >> 3), 64);
+        const uint32_t nib = ww >> (4 * (lane & 7));
+        f32x4 o;
+        o[0] = (nib & 1u) ? 1.0f : -1.0f;
+        o[1] = (nib & 2u) ? 1.0f : -1.0f;
+        o[2] = (nib & 4u) ? 1.0f : -1.0f;
+        o[3] = (nib & 8u) ? 1.0f : -1.0f;
+        __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(out + k0 + 256 * j + 4 * lane));
     }
 }
 
-typedef void (*vote_kernel_t)(const float*, float*, uint32_t*, int16_t*, const VoteArgs);
-
-template <int V, int COLS, int RU>
-vote_kernel_t pick_nt(int nt)
+// ---------------------------------------------------------------------------------------
+// Measurement aids: a plain streaming read and a plain copy of a buffer of known size.
+// They calibrate what the HBM counters report per byte and give the bandwidth a trivially
+// linear access pattern reaches on the same device, next to which the vote kernel is judged.
+// ---------------------------------------------------------------------------------------
+template <bool NT>
+__global__ void __launch_bounds__(kBlock)
+probe_read_kernel(const f32x4* __restrict__ src, int64_t nvec, int64_t per_block, float* sink)
 {
-    return nt ? brace_vote_kernel<V, COLS, RU, true> : brace_vote_kernel<V, COLS, RU, false>;
+    const int64_t begin = (int64_t)blockIdx.x * per_block;
+    int64_t end = begin + per_block;
+    if (end > nvec)
+        end = nvec;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    int64_t i = begin + threadIdx.x;
+    for (; i + 7 * kBlock < end; i += 8 * kBlock) {
+        f32x4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            v[u] = NT ? __builtin_nontemporal_load(src + i + u * kBlock) : src[i + u * kBlock];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            acc += v[u];
+    }
+    for (; i < end; i += kBlock)
+        acc += NT ? __builtin_nontemporal_load(src + i) : src[i];
+    const float t = acc[0] + acc[1] + acc[2] + acc[3];
+    if (t == 123456789.0f)           // practically never: keeps the loads alive
+        sink[0] = t;
 }
 
-template <int V, int COLS>
-vote_kernel_t pick_ru(int ru, int nt)
+__global__ void __launch_bounds__(kBlock)
+probe_copy_kernel(f32x4* __restrict__ dst, const f32x4* __restrict__ src, int64_t nvec,
+                  int64_t per_block)
 {
-    switch (ru) {
-    case 2: return pick_nt<V, COLS, 2>(nt);
-    case 4: return pick_nt<V, COLS, 4>(nt);
-    case 16: return pick_nt<V, COLS, 16>(nt);
-    default: return pick_nt<V, COLS, 8>(nt);
+    const int64_t begin = (int64_t)blockIdx.x * per_block;
+    int64_t end = begin + per_block;
+    if (end > nvec)
+        end = nvec;
+    int64_t i = begin + threadIdx.x;
+    for (; i + 3 * kBlock < end; i += 4 * kBlock) {
+        f32x4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            v[u] = __builtin_nontemporal_load(src + i + u * kBlock);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            __builtin_nontemporal_store(v[u], dst + i + u * kBlock);
     }
-}
-
-template <int V>
-vote_kernel_t pick_cols(int cols, int ru, int nt)
-{
-    switch (cols) {
-    case 1: return pick_ru<V, 1>(ru, nt);
-    case 4: return pick_ru<V, 4>(ru, nt);
-    default: return pick_ru<V, 2>(ru, nt);
-    }
-}
-
-vote_kernel_t pick_kernel(int v, int cols, int ru, int nt)
-{
-    switch (v) {
-    case 4: return pick_cols<4>(cols, ru, nt);
-    case 2: return pick_cols<2>(cols, ru, nt);
-    default: return pick_cols<1>(cols, ru, nt);
-    }
+    for (; i < end; i += kBlock)
+        dst[i] = src[i];
 }
 
 bool aligned_to(const void* p, uintptr_t bytes)
@@ -401,7 +230,17 @@ int launch_range(const float* updates, int64_t n, int64_t d, int64_t ld, int thr
     }
     if (t.vec == 1 || t.vec == 2 || t.vec == 4)
         v = v < t.vec ? v : t.vec;
-    const int cols = (t.cols == 1 || t.cols == 4) ? t.cols : 2;
+
+    uint32_t* bits = static_cast<uint32_t*>(p->out_bits_dev);
+
+    // Split the writes off the read stream?  Needs float output, 16-byte aligned, and whole
+    // 1024-coordinate groups; worth it only for large ranges unless forced.
+    const int64_t lo_s = (lo + kGroup - 1) / kGroup * kGroup;
+    const int64_t hi_s = hi / kGroup * kGroup;
+    const int64_t groups = hi_s > lo_s ? (hi_s - lo_s) / kGroup : 0;
+    bool split = out && aligned_to(out, 16) && groups > 0 && t.split_writes != 1;
+    if (split && t.split_writes != 2)
+        split = groups >= kSplitMinGroups;
 
     VoteArgs a;
     a.ld = ld;
@@ -412,39 +251,67 @@ int launch_range(const float* updates, int64_t n, int64_t d, int64_t ld, int thr
     a.lo = lo;
     a.hi = hi;
     a.d = d;
-    uint32_t* bits = static_cast<uint32_t*>(p->out_bits_dev);
+    a.split = split ? 1 : 0;
+    a.reserved = 0;
 
     const int64_t slot = 64 * (int64_t)v;
-    int64_t lo_a = (lo + slot - 1) / slot * slot;
-    int64_t hi_a = hi / slot * slot;
-    if (lo_a >= hi_a)
-        lo_a = hi_a = lo;          // no body: everything is "tail" edge
+    int64_t lo_a, hi_a;
+    if (split) {
+        lo_a = lo_s;
+        hi_a = hi_s;
+    } else {
+        lo_a = (lo + slot - 1) / slot * slot;
+        hi_a = hi / slot * slot;
+        if (lo_a >= hi_a)
+            lo_a = hi_a = lo;      // no body: everything is "tail" edge
+    }
     a.lo_a = lo_a;
     a.hi_a = hi_a;
 
     const int64_t slots = (hi_a - lo_a) / slot;
-    const int64_t per_block = (int64_t)kWaves * cols;
-    int64_t body_blocks = (slots + per_block - 1) / per_block;
-    if (a.swizzle)                 // the swizzled map needs a multiple of 8 tiles' worth of ids
-        body_blocks = (body_blocks + kXcds - 1) / kXcds * kXcds;
+    const int64_t per_block = (int64_t)kWaves * t.cols;
+    int64_t tiles = (slots + per_block - 1) / per_block;
+    if (a.swizzle)                 // the swizzled map needs a multiple of 8 tile ids
+        tiles = (tiles + kXcds - 1) / kXcds * kXcds;
+    int64_t body_blocks = tiles;
+    if (t.persist > 0) {
+        const int64_t resident = (int64_t)t.persist * compute_units();
+        if (resident > 0 && body_blocks > resident)
+            body_blocks = resident;
+    }
+    a.tiles = tiles;
     a.body_blocks = body_blocks;
 
     int64_t edge = (lo_a - lo) + (hi - hi_a);
     if (bits && hi == d)
         edge += ((d + 31) & ~(int64_t)31) - d;
-    const int64_t edge_blocks = (edge + kBlock - 1) / kBlock;
-    const int64_t grid = body_blocks + edge_blocks;
+    a.edge_blocks = (edge + kBlock - 1) / kBlock;
+    const int64_t grid = body_blocks + a.edge_blocks;
     if (grid <= 0)
         return BRACE_OK;
     if (grid > 0x7fffffffLL)
         return fail(BRACE_ERANGE, "range needs %lld blocks, more than one launch can hold",
                     (long long)grid);
 
-    vote_kernel_t k = pick_kernel(v, cols, t.unroll, t.nontemporal);
-    hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(kBlock), 0, stream, updates, out, bits, p->sums_dev, a);
-    const hipError_t err = hipGetLastError();
+    vote_kernel_t k;
+    switch (v) {
+    case 4: k = brace_vote_pick_v4(t.cols, t.unroll, t.nontemporal, t.pipeline); break;
+    case 2: k = brace_vote_pick_v2(t.cols, t.unroll, t.nontemporal, t.pipeline); break;
+    default: k = brace_vote_pick_v1(t.cols, t.unroll, t.nontemporal, t.pipeline); break;
+    }
+    hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(kBlock), 0, stream, updates, out, bits,
+                       p->sums_dev, a);
+    hipError_t err = hipGetLastError();
     if (err != hipSuccess)
         return fail(BRACE_EHIP, "kernel launch failed: %s", hipGetErrorString(err));
+    if (split) {
+        const int64_t egrid = (groups + kWaves - 1) / kWaves;
+        hipLaunchKernelGGL(brace_expand_kernel, dim3((unsigned)egrid), dim3(kBlock), 0, stream,
+                           out, static_cast<const uint32_t*>(bits), lo_s, groups);
+        err = hipGetLastError();
+        if (err != hipSuccess)
+            return fail(BRACE_EHIP, "expand kernel launch failed: %s", hipGetErrorString(err));
+    }
     return BRACE_OK;
 }
 
@@ -534,9 +401,10 @@ int brace_set_tuning(const brace_tuning_t* tuning)
         return fail(BRACE_EINVAL, "tuning->struct_size is %u, expected %zu", tuning->struct_size,
                     sizeof(brace_tuning_t));
     const int v = tuning->vec, c = tuning->cols, u = tuning->unroll;
-    if (!(v == 0 || v == 1 || v == 2 || v == 4) || !(c == 1 || c == 2 || c == 4) ||
-        !(u == 2 || u == 4 || u == 8 || u == 16))
-        return fail(BRACE_EINVAL, "tuning: vec in {0,1,2,4}, cols in {1,2,4}, unroll in {2,4,8,16}");
+    if (!(v == 0 || v == 1 || v == 2 || v == 4) || !(c == 1 || c == 2 || c == 4 || c == 8) ||
+        !(u == 2 || u == 4 || u == 8) || tuning->persist < 0 || tuning->persist > 64 ||
+        tuning->split_writes < 0 || tuning->split_writes > 2)
+        return fail(BRACE_EINVAL, "tuning: vec in {0,1,2,4}, cols in {1,2,4,8}, unroll in {2,4,8}, persist in [0,64], split_writes in {0,1,2}");
     g_tuning = *tuning;
     return BRACE_OK;
 }
@@ -546,6 +414,55 @@ int brace_get_tuning(brace_tuning_t* tuning)
     if (!tuning)
         return fail(BRACE_EINVAL, "tuning is NULL");
     *tuning = g_tuning;
+    return BRACE_OK;
+}
+
+int brace_probe_read(const void* src_dev, int64_t nbytes, int32_t nontemporal, void* sink_dev,
+                     void* hip_stream)
+{
+    if (!src_dev || !sink_dev || nbytes < 0 || (nbytes & 15) || !aligned_to(src_dev, 16) ||
+        !aligned_to(sink_dev, 4))
+        return fail(BRACE_EINVAL, "probe_read: need 16-byte aligned src, nbytes %% 16 == 0, a sink");
+    const int64_t nvec = nbytes / 16;
+    if (nvec == 0)
+        return BRACE_OK;
+    const int64_t per_block = 8 * kBlock * 4;                 // 128 KiB per block
+    const int64_t grid = (nvec + per_block - 1) / per_block;
+    if (grid > 0x7fffffffLL)
+        return fail(BRACE_ERANGE, "probe_read: buffer too large for one launch");
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (nontemporal)
+        hipLaunchKernelGGL(probe_read_kernel<true>, dim3((unsigned)grid), dim3(kBlock), 0, st,
+                           static_cast<const f32x4*>(src_dev), nvec, per_block,
+                           static_cast<float*>(sink_dev));
+    else
+        hipLaunchKernelGGL(probe_read_kernel<false>, dim3((unsigned)grid), dim3(kBlock), 0, st,
+                           static_cast<const f32x4*>(src_dev), nvec, per_block,
+                           static_cast<float*>(sink_dev));
+    const hipError_t err = hipGetLastError();
+    if (err != hipSuccess)
+        return fail(BRACE_EHIP, "probe_read launch failed: %s", hipGetErrorString(err));
+    return BRACE_OK;
+}
+
+int brace_probe_copy(void* dst_dev, const void* src_dev, int64_t nbytes, void* hip_stream)
+{
+    if (!src_dev || !dst_dev || nbytes < 0 || (nbytes & 15) || !aligned_to(src_dev, 16) ||
+        !aligned_to(dst_dev, 16))
+        return fail(BRACE_EINVAL, "probe_copy: need 16-byte aligned buffers, nbytes %% 16 == 0");
+    const int64_t nvec = nbytes / 16;
+    if (nvec == 0)
+        return BRACE_OK;
+    const int64_t per_block = 4 * kBlock * 4;                 // 64 KiB per block
+    const int64_t grid = (nvec + per_block - 1) / per_block;
+    if (grid > 0x7fffffffLL)
+        return fail(BRACE_ERANGE, "probe_copy: buffer too large for one launch");
+    hipLaunchKernelGGL(probe_copy_kernel, dim3((unsigned)grid), dim3(kBlock), 0,
+                       static_cast<hipStream_t>(hip_stream), static_cast<f32x4*>(dst_dev),
+                       static_cast<const f32x4*>(src_dev), nvec, per_block);
+    const hipError_t err = hipGetLastError();
+    if (err != hipSuccess)
+        return fail(BRACE_EHIP, "probe_copy launch failed: %s", hipGetErrorString(err));
     return BRACE_OK;
 }
 

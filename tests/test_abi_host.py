@@ -49,7 +49,7 @@ def test_struct_layouts_match_the_header():
     assert B.BraceParams.ld.offset == 16
     assert B.BraceParams.out_bits_dev.offset == 24
     assert B.BraceParams.sums_dev.offset == 32
-    assert ctypes.sizeof(B.BraceTuning) == 24
+    assert ctypes.sizeof(B.BraceTuning) == 36
 
 
 def test_params_init_defaults(L):
@@ -137,10 +137,17 @@ def test_degenerate_sizes_are_accepted_without_a_launch(L):
 def test_tuning_roundtrip_and_validation(L):
     B.brace_reset_tuning()
     base = B.brace_get_tuning()
-    assert base == {"vec": 0, "cols": 2, "unroll": 8, "nontemporal": 1, "xcd_swizzle": 0}
-    B.brace_set_tuning(vec=2, cols=4, unroll=16, nontemporal=0, xcd_swizzle=1)
-    assert B.brace_get_tuning() == {"vec": 2, "cols": 4, "unroll": 16, "nontemporal": 0,
-                                    "xcd_swizzle": 1}
+    assert set(base) == {"vec", "cols", "unroll", "nontemporal", "xcd_swizzle", "persist",
+                         "pipeline", "split_writes"}
+    B.brace_set_tuning(vec=2, cols=4, unroll=8, nontemporal=0, xcd_swizzle=1, persist=3,
+                       pipeline=0, split_writes=2)
+    assert B.brace_get_tuning() == {"vec": 2, "cols": 4, "unroll": 8, "nontemporal": 0,
+                                    "xcd_swizzle": 1, "persist": 3, "pipeline": 0,
+                                    "split_writes": 2}
+    with pytest.raises(B.BraceError):
+        B.brace_set_tuning(split_writes=3)
+    with pytest.raises(B.BraceError):
+        B.brace_set_tuning(persist=-1)
     with pytest.raises(B.BraceError):
         B.brace_set_tuning(vec=3)
     with pytest.raises(B.BraceError):

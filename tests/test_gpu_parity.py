@@ -198,6 +198,37 @@ def test_single_chunk_touches_only_its_range():
     assert got_bits[:lo].all() and got_bits[hi:].all()      # untouched bits keep their 1s
 
 
+@pytest.mark.parametrize("n,d,offset", [(5, 1024, 0), (5, 1023, 0), (7, 5000, 0), (9, 40_000, 4),
+                                        (9, 40_001, 8), (3, 2048 + 1, 0), (12, 100_003, 0)])
+def test_split_write_path_bit_exact(n, d, offset):
+    # Force the two-kernel path (bits first, floats expanded afterwards) on small inputs,
+    # with and without a separate bit array (without it the bit-words are parked in `out`).
+    upd = special_matrix(n, d, seed=n * 31 + d)
+    want = O.brace_direct(upd.cpu().numpy(), 1.0)
+    try:
+        B.brace_set_tuning(split_writes=2)
+        guard = torch.full((d + 64 + offset,), 3.0, device=DEV, dtype=torch.float32)
+        out = guard[32 + offset: 32 + offset + d]
+        for with_bits in (False, True):
+            guard.fill_(3.0)
+            bits = torch.full(((d + 31) // 32,), -1, device=DEV, dtype=torch.int32) if with_bits else None
+            B.brace_aggregate(upd, 0, 1.0, out=out, out_bits=bits)
+            torch.cuda.synchronize()
+            g = guard.cpu().numpy()
+            assert np.array_equal(g[32 + offset: 32 + offset + d], want.out), with_bits
+            assert (g[: 32 + offset] == 3.0).all() and (g[32 + offset + d:] == 3.0).all()
+            if with_bits:
+                assert np.array_equal(bits.cpu().numpy().view(np.uint8)[: (d + 7) // 8], want.bits)
+        # chunk by chunk through the same forced path
+        chunked = torch.full((d,), 7.0, device=DEV, dtype=torch.float32)
+        for c in range(n):
+            B.brace_aggregate_chunk(upd, 0, c, 1.0, out=chunked)
+        torch.cuda.synchronize()
+        assert np.array_equal(chunked.cpu().numpy(), want.out)
+    finally:
+        B.brace_reset_tuning()
+
+
 # --------------------------------------------------------------------------
 # Every launch tuning computes the same thing
 # --------------------------------------------------------------------------
@@ -209,16 +240,20 @@ def test_all_tunings_agree_with_the_oracle():
             view = special_matrix(n, d, seed=ld + off, ld=ld, offset=off)
             want = O.brace_direct(view.cpu().numpy(), 2.0)
             for vec in (0, 1, 2, 4):
-                for cols in (1, 2, 4):
-                    for unroll in (2, 4, 8, 16):
-                        for nt in (0, 1):
-                            for sw in (0, 1):
-                                B.brace_set_tuning(vec, cols, unroll, nt, sw)
-                                out, bits, sums = gpu_aggregate(view, 0, 2.0)
-                                tag = (ld, off, vec, cols, unroll, nt, sw)
-                                assert np.array_equal(out, want.out), tag
-                                assert np.array_equal(sums.astype(np.int64), want.sums), tag
-                                assert np.array_equal(bits[: (d + 7) // 8], want.bits), tag
+                for cols in (1, 2, 4, 8):
+                    for unroll in (2, 4, 8):
+                        for nt, sw, persist, pipe, split in (
+                                (0, 0, 0, 0, 1), (1, 0, 0, 0, 2), (1, 1, 0, 1, 1), (1, 0, 1, 0, 2),
+                                (0, 1, 2, 1, 2), (1, 0, 0, 1, 0)):
+                            B.brace_set_tuning(vec, cols, unroll, nt, sw, persist, pipe, split)
+                            out, bits, sums = gpu_aggregate(view, 0, 2.0)
+                            tag = (ld, off, vec, cols, unroll, nt, sw, persist, pipe, split)
+                            assert np.array_equal(out, want.out), tag
+                            assert np.array_equal(sums.astype(np.int64), want.sums), tag
+                            assert np.array_equal(bits[: (d + 7) // 8], want.bits), tag
+                            out, _, _ = gpu_aggregate(view, 0, 2.0, want_bits=False,
+                                                      want_sums=False)
+                            assert np.array_equal(out, want.out), tag
     finally:
         B.brace_reset_tuning()
 
