@@ -105,6 +105,24 @@ int brace_chunk_range(int64_t n, int64_t d, int64_t chunk, int64_t* lo, int64_t*
  */
 int brace_chunk_owner(int64_t n, int64_t chunk, int64_t* owner_client);
 
+/*
+ * The operation BRACE replaces: plain ring-all-reduce aggregation (Sec. 2.2), out[k] =
+ * sum_i updates[i][k], or the Mean rule of Sec. 2.1 (sum / n) with mean = 1.  Same streaming
+ * shape and chunking as brace_aggregate.  Accumulation is in fp64 and the result is rounded
+ * to fp32 once, so it matches an fp64 reference within fp32 rounding whatever the
+ * cancellation between rows.
+ */
+typedef struct brace_rar_params {
+    uint32_t struct_size;  /* sizeof(brace_rar_params_t); checked                              */
+    int32_t  mean;         /* 0: sum (Sec. 2.2), 1: mean (Sec. 2.1)                             */
+    int64_t  ld;           /* row pitch in elements; 0 means ld = d                              */
+} brace_rar_params_t;
+
+int brace_rar_aggregate(const float* updates_dev, int64_t n, int64_t d,
+                        const brace_rar_params_t* params, float* out_dev, void* hip_stream);
+int brace_rar_aggregate_chunk(const float* updates_dev, int64_t n, int64_t d, int64_t chunk,
+                              const brace_rar_params_t* params, float* out_dev, void* hip_stream);
+
 /* Text of the last error on the calling thread ("" if none).  Static storage; do not free. */
 const char* brace_last_error(void);
 

@@ -44,6 +44,14 @@ class BraceTuning(ctypes.Structure):
     ]
 
 
+class BraceRarParams(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", ctypes.c_uint32),
+        ("mean", ctypes.c_int32),
+        ("ld", ctypes.c_int64),
+    ]
+
+
 class BraceError(RuntimeError):
     def __init__(self, code: int, text: str):
         super().__init__(f"brace status {code}: {text}")
@@ -56,7 +64,7 @@ _lib = None
 EXPORTS = (
     "brace_params_init", "brace_aggregate", "brace_aggregate_chunk", "brace_chunk_range",
     "brace_chunk_owner", "brace_last_error", "brace_set_tuning", "brace_get_tuning",
-    "brace_probe_read", "brace_probe_copy",
+    "brace_probe_read", "brace_probe_copy", "brace_rar_aggregate", "brace_rar_aggregate_chunk",
 )
 
 
@@ -98,6 +106,11 @@ def lib():
     L.brace_probe_read.restype = ctypes.c_int
     L.brace_probe_copy.argtypes = [vp, vp, i64, vp]
     L.brace_probe_copy.restype = ctypes.c_int
+    rp = ctypes.POINTER(BraceRarParams)
+    L.brace_rar_aggregate.argtypes = [vp, i64, i64, rp, vp, vp]
+    L.brace_rar_aggregate.restype = ctypes.c_int
+    L.brace_rar_aggregate_chunk.argtypes = [vp, i64, i64, i64, rp, vp, vp]
+    L.brace_rar_aggregate_chunk.restype = ctypes.c_int
     _lib = L
     return L
 
@@ -209,3 +222,16 @@ def brace_probe_copy(dst, src, stream=None):
     """Plain copy of a whole device tensor (measurement aid)."""
     nbytes = src.numel() * src.element_size()
     _check(lib().brace_probe_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream_handle(stream)))
+
+
+def brace_rar_aggregate(updates, out, mean: bool = False, chunk: int | None = None, stream=None):
+    """Plain ring-all-reduce sum (or mean) of the n client rows; `out` is the full vector."""
+    n, d, ld = _matrix(updates)
+    p = BraceRarParams(ctypes.sizeof(BraceRarParams), 1 if mean else 0, ld)
+    if chunk is None:
+        _check(lib().brace_rar_aggregate(updates.data_ptr(), n, d, ctypes.byref(p), _ptr(out),
+                                         _stream_handle(stream)))
+    else:
+        _check(lib().brace_rar_aggregate_chunk(updates.data_ptr(), n, d, chunk, ctypes.byref(p),
+                                               _ptr(out), _stream_handle(stream)))
+    return out

@@ -9,7 +9,8 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
-SOURCES = ["brace.hip", "vote_v1.hip", "vote_v2.hip", "vote_v4.hip"]
+SOURCES = ["brace.hip", "vote_v4.hip", "sum_v4.hip", "vote_v2.hip", "sum_v2.hip", "vote_v1.hip",
+           "sum_v1.hip"]
 OBJDIR = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libbrace.so")
 

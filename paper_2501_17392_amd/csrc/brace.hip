@@ -1,6 +1,7 @@
 // BRACE robust chunk aggregation for MI355X (gfx950): C ABI, host logic, and the small
-// kernels (bit expansion, measurement aids).  The streaming vote kernel lives in
-// vote_kernel.hpp and is instantiated per load width in vote_v{1,2,4}.hip.
+// kernels (bit expansion, measurement aids).  The streaming skeleton lives in
+// stream_kernel.hpp, the vote and sum operations in ops.hpp; they are instantiated per
+// load width in vote_v{1,2,4}.hip and sum_v{1,2,4}.hip.
 
 #include <hip/hip_runtime.h>
 
@@ -11,7 +12,7 @@
 #include <cstring>
 
 #include "brace.h"
-#include "vote_kernel.hpp"
+#include "ops.hpp"
 
 namespace {
 
@@ -210,65 +211,44 @@ int validate(const float* updates, int64_t n, int64_t d, int64_t f, const brace_
     return BRACE_OK;
 }
 
-int launch_range(const float* updates, int64_t n, int64_t d, int64_t ld, int thresh,
-                 const brace_params_t* p, float* out, int64_t lo, int64_t hi, hipStream_t stream)
+// Widest load (in dwords) that the matrix and every vector store of `bytes_per_coord`-sized
+// outputs can use, capped by the tuning.
+int pick_width(const float* updates, int64_t n, int64_t ld, const void* out4, const void* out2,
+               int cap)
 {
-    if (hi <= lo)
-        return BRACE_OK;
-    const brace_tuning_t t = g_tuning;
-
-    // Widest load every row, every slot and every vector store can use.
     int v = 4;
     while (v > 1) {
         const uintptr_t bytes = 4u * v;
         const bool ok = aligned_to(updates, bytes) && (ld % v == 0 || n == 1) &&
-                        (!out || aligned_to(out, bytes)) &&
-                        (!p->sums_dev || aligned_to(p->sums_dev, 2u * v));
+                        (!out4 || aligned_to(out4, bytes)) && (!out2 || aligned_to(out2, 2u * v));
         if (ok)
             break;
         v >>= 1;
     }
-    if (t.vec == 1 || t.vec == 2 || t.vec == 4)
-        v = v < t.vec ? v : t.vec;
+    if (cap == 1 || cap == 2 || cap == 4)
+        v = v < cap ? v : cap;
+    return v;
+}
 
-    uint32_t* bits = static_cast<uint32_t*>(p->out_bits_dev);
-
-    // Split the writes off the read stream?  Needs float output, 16-byte aligned, and whole
-    // 1024-coordinate groups; worth it only for large ranges unless forced.
-    const int64_t lo_s = (lo + kGroup - 1) / kGroup * kGroup;
-    const int64_t hi_s = hi / kGroup * kGroup;
-    const int64_t groups = hi_s > lo_s ? (hi_s - lo_s) / kGroup : 0;
-    bool split = out && aligned_to(out, 16) && groups > 0 && t.split_writes != 1;
-    if (split && t.split_writes != 2)
-        split = groups >= kSplitMinGroups;
-
-    VoteArgs a;
+// Geometry of one launch over [lo, hi): body aligned to `unit` coordinates (a multiple of the
+// wave slot 64*v), edges first, optional padding [hi, hi_ext) for the op.  Returns the grid.
+int64_t plan_range(StreamArgs& a, const brace_tuning_t& t, int64_t n, int64_t ld, int v,
+                   int64_t unit, int64_t lo, int64_t hi, int64_t hi_ext)
+{
     a.ld = ld;
     a.n = (int32_t)n;
-    a.thresh = thresh;
-    a.zero_sign = p->zero_sign;
     a.swizzle = t.xcd_swizzle ? 1 : 0;
     a.lo = lo;
     a.hi = hi;
-    a.d = d;
-    a.split = split ? 1 : 0;
-    a.reserved = 0;
-
-    const int64_t slot = 64 * (int64_t)v;
-    int64_t lo_a, hi_a;
-    if (split) {
-        lo_a = lo_s;
-        hi_a = hi_s;
-    } else {
-        lo_a = (lo + slot - 1) / slot * slot;
-        hi_a = hi / slot * slot;
-        if (lo_a >= hi_a)
-            lo_a = hi_a = lo;      // no body: everything is "tail" edge
-    }
+    a.hi_ext = hi_ext;
+    int64_t lo_a = (lo + unit - 1) / unit * unit;
+    int64_t hi_a = hi / unit * unit;
+    if (lo_a >= hi_a)
+        lo_a = hi_a = lo;          // no body: everything is "tail" edge
     a.lo_a = lo_a;
     a.hi_a = hi_a;
 
-    const int64_t slots = (hi_a - lo_a) / slot;
+    const int64_t slots = (hi_a - lo_a) / (64 * (int64_t)v);
     const int64_t per_block = (int64_t)kWaves * t.cols;
     int64_t tiles = (slots + per_block - 1) / per_block;
     if (a.swizzle)                 // the swizzled map needs a multiple of 8 tile ids
@@ -281,37 +261,135 @@ int launch_range(const float* updates, int64_t n, int64_t d, int64_t ld, int thr
     }
     a.tiles = tiles;
     a.body_blocks = body_blocks;
-
-    int64_t edge = (lo_a - lo) + (hi - hi_a);
-    if (bits && hi == d)
-        edge += ((d + 31) & ~(int64_t)31) - d;
+    const int64_t edge = (lo_a - lo) + (hi_ext - hi_a);
     a.edge_blocks = (edge + kBlock - 1) / kBlock;
-    const int64_t grid = body_blocks + a.edge_blocks;
+    return body_blocks + a.edge_blocks;
+}
+
+int check_launch(const char* what)
+{
+    const hipError_t err = hipGetLastError();
+    if (err != hipSuccess)
+        return fail(BRACE_EHIP, "%s launch failed: %s", what, hipGetErrorString(err));
+    return BRACE_OK;
+}
+
+int launch_vote(const float* updates, int64_t n, int64_t d, int64_t ld, int thresh,
+                const brace_params_t* p, float* out, int64_t lo, int64_t hi, hipStream_t stream)
+{
+    if (hi <= lo)
+        return BRACE_OK;
+    const brace_tuning_t t = g_tuning;
+    const int v = pick_width(updates, n, ld, out, p->sums_dev, t.vec);
+    uint32_t* bits = static_cast<uint32_t*>(p->out_bits_dev);
+
+    // Split the writes off the read stream?  Needs float output, 16-byte aligned, and whole
+    // 1024-coordinate groups; worth it only for large ranges unless forced.
+    const int64_t lo_s = (lo + kGroup - 1) / kGroup * kGroup;
+    const int64_t hi_s = hi / kGroup * kGroup;
+    const int64_t groups = hi_s > lo_s ? (hi_s - lo_s) / kGroup : 0;
+    bool split = out && aligned_to(out, 16) && groups > 0 && t.split_writes != 1;
+    if (split && t.split_writes != 2)
+        split = groups >= kSplitMinGroups;
+
+    VoteOp op;
+    op.out = out;
+    op.bits = bits;
+    op.sums = p->sums_dev;
+    op.thresh = thresh;
+    op.zero_sign = p->zero_sign;
+    op.split = split ? 1 : 0;
+    op.reserved = 0;
+
+    int64_t hi_ext = hi;
+    if (bits && hi == d)
+        hi_ext = (d + 31) & ~(int64_t)31;          // the last word's padding bits are zeroed
+    StreamArgs a;
+    const int64_t grid = plan_range(a, t, n, ld, v, split ? kGroup : 64 * (int64_t)v, lo, hi,
+                                    hi_ext);
     if (grid <= 0)
         return BRACE_OK;
     if (grid > 0x7fffffffLL)
         return fail(BRACE_ERANGE, "range needs %lld blocks, more than one launch can hold",
                     (long long)grid);
 
-    vote_kernel_t k;
+    stream_kernel_t<VoteOp> k;
     switch (v) {
     case 4: k = brace_vote_pick_v4(t.cols, t.unroll, t.nontemporal, t.pipeline); break;
     case 2: k = brace_vote_pick_v2(t.cols, t.unroll, t.nontemporal, t.pipeline); break;
     default: k = brace_vote_pick_v1(t.cols, t.unroll, t.nontemporal, t.pipeline); break;
     }
-    hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(kBlock), 0, stream, updates, out, bits,
-                       p->sums_dev, a);
-    hipError_t err = hipGetLastError();
-    if (err != hipSuccess)
-        return fail(BRACE_EHIP, "kernel launch failed: %s", hipGetErrorString(err));
+    hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(kBlock), 0, stream, updates, a, op);
+    int rc = check_launch("vote kernel");
+    if (rc != BRACE_OK)
+        return rc;
     if (split) {
         const int64_t egrid = (groups + kWaves - 1) / kWaves;
         hipLaunchKernelGGL(brace_expand_kernel, dim3((unsigned)egrid), dim3(kBlock), 0, stream,
-                           out, static_cast<const uint32_t*>(bits), lo_s, groups);
-        err = hipGetLastError();
-        if (err != hipSuccess)
-            return fail(BRACE_EHIP, "expand kernel launch failed: %s", hipGetErrorString(err));
+                           out, static_cast<const uint32_t*>(bits), a.lo_a, groups);
+        rc = check_launch("expand kernel");
     }
+    return rc;
+}
+
+int launch_sum(const float* updates, int64_t n, int64_t ld, double scale, float* out, int64_t lo,
+               int64_t hi, hipStream_t stream)
+{
+    if (hi <= lo)
+        return BRACE_OK;
+    const brace_tuning_t t = g_tuning;
+    const int v = pick_width(updates, n, ld, out, nullptr, t.vec);
+    SumOp op;
+    op.out = out;
+    op.scale = scale;
+    StreamArgs a;
+    const int64_t grid = plan_range(a, t, n, ld, v, 64 * (int64_t)v, lo, hi, hi);
+    if (grid <= 0)
+        return BRACE_OK;
+    if (grid > 0x7fffffffLL)
+        return fail(BRACE_ERANGE, "range needs %lld blocks, more than one launch can hold",
+                    (long long)grid);
+    stream_kernel_t<SumOp> k;
+    switch (v) {
+    case 4: k = brace_sum_pick_v4(t.cols, t.unroll, t.nontemporal, t.pipeline); break;
+    case 2: k = brace_sum_pick_v2(t.cols, t.unroll, t.nontemporal, t.pipeline); break;
+    default: k = brace_sum_pick_v1(t.cols, t.unroll, t.nontemporal, t.pipeline); break;
+    }
+    hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(kBlock), 0, stream, updates, a, op);
+    return check_launch("sum kernel");
+}
+
+int validate_rar(const float* updates, int64_t n, int64_t d, const brace_rar_params_t* p,
+                 const float* out, int64_t* ld_out, double* scale_out)
+{
+    if (!p)
+        return fail(BRACE_EINVAL, "params is NULL");
+    if (p->struct_size != sizeof(brace_rar_params_t))
+        return fail(BRACE_EINVAL, "params->struct_size is %u, expected %zu", p->struct_size,
+                    sizeof(brace_rar_params_t));
+    if (n < 1)
+        return fail(BRACE_EINVAL, "n must be >= 1 (got %lld)", (long long)n);
+    if (n > BRACE_MAX_CLIENTS)
+        return fail(BRACE_ERANGE, "n = %lld exceeds BRACE_MAX_CLIENTS", (long long)n);
+    if (d < 0)
+        return fail(BRACE_EINVAL, "d must be >= 0 (got %lld)", (long long)d);
+    if (p->mean != 0 && p->mean != 1)
+        return fail(BRACE_EINVAL, "mean must be 0 (sum) or 1 (mean)");
+    if (p->ld != 0 && p->ld < d)
+        return fail(BRACE_EINVAL, "ld = %lld is smaller than d = %lld", (long long)p->ld,
+                    (long long)d);
+    const int64_t ld = p->ld ? p->ld : d;
+    *ld_out = ld;
+    *scale_out = p->mean ? 1.0 / (double)n : 1.0;
+    if (d == 0)
+        return BRACE_OK;
+    if (!updates || !out)
+        return fail(BRACE_EINVAL, "updates_dev or out_dev is NULL");
+    if (!aligned_to(updates, 4) || !aligned_to(out, 4))
+        return fail(BRACE_EINVAL, "updates_dev and out_dev must be 4-byte aligned");
+    const float* in_end = updates + (n - 1) * ld + d;
+    if (out < in_end && updates < out + d)
+        return fail(BRACE_EINVAL, "out_dev overlaps updates_dev");
     return BRACE_OK;
 }
 
@@ -365,7 +443,7 @@ int brace_aggregate(const float* updates_dev, int64_t n, int64_t d, int64_t f,
         return rc;
     // Eq. (1) is per coordinate, so the n chunk aggregations are one pass over [0, d):
     // chunk c's result lands at [lo_c, hi_c) and the chunks tile [0, d).
-    return launch_range(updates_dev, n, d, ld, thresh, params, out_dev, 0, d,
+    return launch_vote(updates_dev, n, d, ld, thresh, params, out_dev, 0, d,
                         static_cast<hipStream_t>(hip_stream));
 }
 
@@ -382,8 +460,36 @@ int brace_aggregate_chunk(const float* updates_dev, int64_t n, int64_t d, int64_
     rc = brace_chunk_range(n, d, chunk, &lo, &hi);
     if (rc != BRACE_OK)
         return rc;
-    return launch_range(updates_dev, n, d, ld, thresh, params, out_dev, lo, hi,
+    return launch_vote(updates_dev, n, d, ld, thresh, params, out_dev, lo, hi,
                         static_cast<hipStream_t>(hip_stream));
+}
+
+int brace_rar_aggregate(const float* updates_dev, int64_t n, int64_t d,
+                        const brace_rar_params_t* params, float* out_dev, void* hip_stream)
+{
+    int64_t ld;
+    double scale;
+    const int rc = validate_rar(updates_dev, n, d, params, out_dev, &ld, &scale);
+    if (rc != BRACE_OK)
+        return rc;
+    return launch_sum(updates_dev, n, ld, scale, out_dev, 0, d,
+                      static_cast<hipStream_t>(hip_stream));
+}
+
+int brace_rar_aggregate_chunk(const float* updates_dev, int64_t n, int64_t d, int64_t chunk,
+                              const brace_rar_params_t* params, float* out_dev, void* hip_stream)
+{
+    int64_t ld;
+    double scale;
+    int rc = validate_rar(updates_dev, n, d, params, out_dev, &ld, &scale);
+    if (rc != BRACE_OK)
+        return rc;
+    int64_t lo, hi;
+    rc = brace_chunk_range(n, d, chunk, &lo, &hi);
+    if (rc != BRACE_OK)
+        return rc;
+    return launch_sum(updates_dev, n, ld, scale, out_dev, lo, hi,
+                      static_cast<hipStream_t>(hip_stream));
 }
 
 const char* brace_last_error(void)

@@ -1,0 +1,157 @@
+// The per-coordinate operations plugged into the streaming skeleton.
+//
+//   VoteOp  BRACE: sign quantisation (Sec. 3 Phase I), sign-sum over the clients
+//           (Phase II), consensus map of Eq. (1) (Phase III), result placed at the
+//           coordinate's position in the global update (Phase IV).
+//   SumOp   the operation BRACE replaces: the plain ring-all-reduce sum of Sec. 2.2, or the
+//           Mean rule of Sec. 2.1 when scaled by 1/n.
+
+#pragma once
+
+#include "stream_kernel.hpp"
+
+namespace brace_dev {
+
+constexpr int kGroup = 1024;                // coordinates whose 32 bit-words fill one 128 B line
+
+// Where the bit-word of coordinates [32j, 32j+32) lives when the floats' own buffer is used
+// as scratch: the 32 words of a 1024-coordinate group sit in the first 128 bytes of the
+// 4 KiB that the group expands to, so the expansion of a group only overwrites its own words.
+__device__ __forceinline__ int64_t scratch_word(int64_t k)
+{
+    return (k & ~(int64_t)(kGroup - 1)) + ((k & (kGroup - 1)) >> 5);
+}
+
+struct VoteOp {
+    float* out;             // d floats, may be null
+    uint32_t* bits;         // packed result, may be null
+    int16_t* sums;          // sign-sums, may be null
+    int32_t thresh;         // result is +1 iff S >= thresh  (thresh = floor(lambda) + 1)
+    int32_t zero_sign;      // vote of +-0 and NaN
+    int32_t split;          // 1: the body emits bit-words only (a second kernel writes the floats)
+    int32_t reserved;
+
+    // Two counters per coordinate: clients voting +1 and clients voting -1.
+    struct State { int pos, neg; };
+
+    __device__ static __forceinline__ void init(State& s) { s.pos = 0; s.neg = 0; }
+
+    // Phase I + II: compares (not a sign-bit test) so that -0.0 and NaN land in neither count.
+    __device__ static __forceinline__ void add(State& s, float v)
+    {
+        s.pos += (v > 0.0f) ? 1 : 0;
+        s.neg += (v < 0.0f) ? 1 : 0;
+    }
+
+    __device__ __forceinline__ int sign_sum(const State& s, int n) const
+    {
+        return s.pos - s.neg + zero_sign * (n - s.pos - s.neg);
+    }
+
+    template <int V, bool NT>
+    __device__ __forceinline__ void store_body(int64_t k, const State (&st)[V], int lane, int n) const
+    {
+        typedef typename Vec<V>::type VT;
+        int s[V];
+        uint32_t mybits = 0;
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            s[e] = sign_sum(st[e], n);
+            mybits |= (s[e] >= thresh ? 1u : 0u) << e;             // Phase III, Eq. (1)
+        }
+        if (out && !split) {
+            VT o;
+#pragma unroll
+            for (int e = 0; e < V; ++e)
+                set_elem<V>(o, e, (s[e] >= thresh) ? 1.0f : -1.0f);
+            store_vec<NT>(reinterpret_cast<VT*>(out + k), o);
+        }
+        if (sums) {
+            typedef typename IVec<V>::type ST;
+            ST sv;
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                if constexpr (V == 1) sv = (short)s[e]; else sv[e] = (short)s[e];
+            }
+            store_vec<NT>(reinterpret_cast<ST*>(sums + k), sv);
+        }
+        if (bits || split) {
+            // 32/V lanes share one 32-bit word; OR them together, the first lane stores.
+            constexpr int L = 32 / V;
+            uint32_t w = mybits << (V * (lane & (L - 1)));
+#pragma unroll
+            for (int m = 1; m < L; m <<= 1)
+                w |= (uint32_t)__shfl_xor((int)w, m, 64);
+            if ((lane & (L - 1)) == 0) {
+                if (bits)
+                    bits[k >> 5] = w;
+                else
+                    reinterpret_cast<uint32_t*>(out)[scratch_word(k)] = w;
+            }
+        }
+    }
+
+    // Bits are merged atomically: a 32-bit word can be shared with a neighbouring chunk's call.
+    __device__ __forceinline__ void store_edge(int64_t k, const State& st, int n) const
+    {
+        const int s = sign_sum(st, n);
+        const bool up = s >= thresh;
+        if (out)
+            out[k] = up ? 1.0f : -1.0f;
+        if (sums)
+            sums[k] = (int16_t)s;
+        if (bits) {
+            if (up)
+                atomicOr(&bits[k >> 5], 1u << (k & 31));
+            else
+                atomicAnd(&bits[k >> 5], ~(1u << (k & 31)));
+        }
+    }
+
+    // Padding bits of the last 32-bit word are zero.
+    __device__ __forceinline__ void pad_edge(int64_t k) const
+    {
+        if (bits)
+            atomicAnd(&bits[k >> 5], ~(1u << (k & 31)));
+    }
+};
+
+struct SumOp {
+    float* out;             // d floats
+    double scale;           // 1 for the ring-all-reduce sum, 1/n for the Mean rule
+
+    // fp64 accumulator: the fp32 result is then the correctly rounded sum up to one double
+    // rounding, whatever the cancellation between benign and Byzantine rows.
+    struct State { double acc; };
+
+    __device__ static __forceinline__ void init(State& s) { s.acc = 0.0; }
+    __device__ static __forceinline__ void add(State& s, float v) { s.acc += (double)v; }
+
+    template <int V, bool NT>
+    __device__ __forceinline__ void store_body(int64_t k, const State (&st)[V], int, int) const
+    {
+        typedef typename Vec<V>::type VT;
+        VT o;
+#pragma unroll
+        for (int e = 0; e < V; ++e)
+            set_elem<V>(o, e, (float)(st[e].acc * scale));
+        store_vec<NT>(reinterpret_cast<VT*>(out + k), o);
+    }
+
+    __device__ __forceinline__ void store_edge(int64_t k, const State& st, int) const
+    {
+        out[k] = (float)(st.acc * scale);
+    }
+
+    __device__ __forceinline__ void pad_edge(int64_t) const {}
+};
+
+}  // namespace brace_dev
+
+// One translation unit per (op, load width) instantiates its share of the kernels.
+brace_dev::stream_kernel_t<brace_dev::VoteOp> brace_vote_pick_v1(int cols, int ru, int nt, int pipe);
+brace_dev::stream_kernel_t<brace_dev::VoteOp> brace_vote_pick_v2(int cols, int ru, int nt, int pipe);
+brace_dev::stream_kernel_t<brace_dev::VoteOp> brace_vote_pick_v4(int cols, int ru, int nt, int pipe);
+brace_dev::stream_kernel_t<brace_dev::SumOp> brace_sum_pick_v1(int cols, int ru, int nt, int pipe);
+brace_dev::stream_kernel_t<brace_dev::SumOp> brace_sum_pick_v2(int cols, int ru, int nt, int pipe);
+brace_dev::stream_kernel_t<brace_dev::SumOp> brace_sum_pick_v4(int cols, int ru, int nt, int pipe);

@@ -1,0 +1,291 @@
+// Streaming column-reduction skeleton for gfx950: one pass over an n x d fp32 matrix that
+// folds the n client rows of every coordinate into a small per-coordinate state held in
+// registers, then hands the state to an epilogue.  The BRACE vote (Sec. 3, Phases I-IV) and
+// the plain ring-all-reduce sum it replaces (Sec. 2.2) are two "ops" plugged into it.
+//
+// Shape of the work: a pure stream.  The matrix is read exactly once (4*n bytes per
+// coordinate) and a few bytes per coordinate are written, so the bound is HBM bandwidth.
+// There is no reuse, no contraction and no cross-lane traffic in the main loop.
+//
+// Launch layout.  The range [lo, hi) of a call is split in
+//   body  [lo_a, hi_a): whole "wave slots" of 64*V coordinates, aligned from coordinate 0,
+//         read with V-dword loads and no bounds checks;
+//   edges [lo, lo_a) and [hi_a, hi) (+ whatever padding the op asks for): one thread per
+//         coordinate with dword loads, run by the FIRST blocks of the same grid so that
+//         they overlap with the body instead of trailing it.
+// A wave owns COLS adjacent slots, i.e. a contiguous run of 64*V*COLS floats in every row;
+// the row pointer is wave-uniform so row stepping is scalar arithmetic and each load is
+// "scalar base + lane offset".  Rows are requested in batches of RU rows x COLS loads; with
+// PIPE the next batch is requested before the current one is consumed, so a wave never
+// drains its outstanding loads between batches.
+//
+// An op provides
+//   struct State;                                  per-coordinate accumulator
+//   static void init(State&);
+//   static void add(State&, float);                fold one client's value
+//   template <int V, bool NT> void store_body(int64_t k, const State (&)[V], int lane, int n) const;
+//                                                  lane's V consecutive coordinates from k
+//   void store_edge(int64_t k, const State&, int n) const;     one coordinate
+//   void pad_edge(int64_t k) const;                coordinate in [hi, hi_ext): op-specific padding
+
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace brace_dev {
+
+#ifndef BRACE_BLOCK
+#define BRACE_BLOCK 256
+#endif
+constexpr int kBlock = BRACE_BLOCK;         // threads per block (waves of 64)
+constexpr int kWaves = kBlock / 64;
+constexpr int kXcds = 8;                    // MI355X: 8 XCDs, blocks are dealt round-robin
+
+template <int V> struct Vec;
+template <> struct Vec<1> { typedef float type; };
+template <> struct Vec<2> { typedef float type __attribute__((ext_vector_type(2))); };
+template <> struct Vec<4> { typedef float type __attribute__((ext_vector_type(4))); };
+
+template <int V> struct IVec;
+template <> struct IVec<1> { typedef short type; };
+template <> struct IVec<2> { typedef short type __attribute__((ext_vector_type(2))); };
+template <> struct IVec<4> { typedef short type __attribute__((ext_vector_type(4))); };
+
+template <int V>
+__device__ __forceinline__ float elem(const typename Vec<V>::type& v, int e)
+{
+    if constexpr (V == 1) return v; else return v[e];
+}
+
+template <int V>
+__device__ __forceinline__ void set_elem(typename Vec<V>::type& v, int e, float x)
+{
+    if constexpr (V == 1) v = x; else v[e] = x;
+}
+
+template <int V, bool NT>
+__device__ __forceinline__ typename Vec<V>::type load_vec(const float* p)
+{
+    typedef typename Vec<V>::type T;
+    if constexpr (NT)
+        return __builtin_nontemporal_load(reinterpret_cast<const T*>(p));
+    else
+        return *reinterpret_cast<const T*>(p);
+}
+
+template <bool NT, typename T>
+__device__ __forceinline__ void store_vec(T* p, const T& v)
+{
+    if constexpr (NT)
+        __builtin_nontemporal_store(v, p);
+    else
+        *p = v;
+}
+
+// Scalars of one launch that do not depend on the op.
+struct StreamArgs {
+    int64_t ld;             // row i at updates + i*ld
+    int32_t n;
+    int32_t swizzle;        // XCD-aware block -> tile map
+    int64_t lo, hi;         // coordinates of this call
+    int64_t lo_a, hi_a;     // aligned body
+    int64_t hi_ext;         // edges run up to here; [hi, hi_ext) is op-specific padding
+    int64_t edge_blocks;    // blocks [0, edge_blocks) run the edges, the rest the body
+    int64_t body_blocks;    // blocks that run the body
+    int64_t tiles;          // tiles in the body; body block b takes tiles b, b + body_blocks, ...
+};
+
+// One wave: COLS adjacent slots starting at wave-uniform coordinate k0.
+template <class Op, int V, int COLS, int RU, bool NT, bool PIPE>
+__device__ __forceinline__ void stream_slots(const float* __restrict__ updates, int64_t ld, int n,
+                                             int64_t k0, int lane, const Op& op)
+{
+    typedef typename Vec<V>::type VT;
+    typedef typename Op::State State;
+    State st[COLS][V];
+#pragma unroll
+    for (int c = 0; c < COLS; ++c)
+#pragma unroll
+        for (int e = 0; e < V; ++e)
+            Op::init(st[c][e]);
+
+    const float* row = updates + k0;            // wave-uniform
+    const uint32_t loff = (uint32_t)lane * V;   // per lane, in elements
+
+    auto load_batch = [&](VT (&x)[RU][COLS]) {
+#pragma unroll
+        for (int r = 0; r < RU; ++r)
+#pragma unroll
+            for (int c = 0; c < COLS; ++c)
+                x[r][c] = load_vec<V, NT>(row + (int64_t)r * ld + loff + c * (64 * V));
+        row += (int64_t)RU * ld;
+        // keep every load of the batch in flight before the first use waits on one
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto fold = [&](const VT (&x)[RU][COLS]) {
+#pragma unroll
+        for (int r = 0; r < RU; ++r)
+#pragma unroll
+            for (int c = 0; c < COLS; ++c)
+#pragma unroll
+                for (int e = 0; e < V; ++e)
+                    Op::add(st[c][e], elem<V>(x[r][c], e));
+    };
+
+    int i = 0;
+    if constexpr (PIPE) {
+        if (n >= RU) {
+            VT xa[RU][COLS], xb[RU][COLS];
+            load_batch(xa);
+            i = RU;                             // rows [0, i) are requested
+            while (i + 2 * RU <= n) {
+                load_batch(xb);
+                fold(xa);
+                load_batch(xa);
+                fold(xb);
+                i += 2 * RU;
+            }
+            if (i + RU <= n) {
+                load_batch(xb);
+                i += RU;
+                fold(xa);
+                fold(xb);
+            } else {
+                fold(xa);
+            }
+        }
+    } else {
+        for (; i + RU <= n; i += RU) {
+            VT x[RU][COLS];
+            load_batch(x);
+            fold(x);
+        }
+    }
+    for (; i < n; ++i) {
+        VT x[COLS];
+#pragma unroll
+        for (int c = 0; c < COLS; ++c)
+            x[c] = load_vec<V, NT>(row + loff + c * (64 * V));
+#pragma unroll
+        for (int c = 0; c < COLS; ++c)
+#pragma unroll
+            for (int e = 0; e < V; ++e)
+                Op::add(st[c][e], elem<V>(x[c], e));
+        row += ld;
+    }
+
+#pragma unroll
+    for (int c = 0; c < COLS; ++c)
+        op.template store_body<V, NT>(k0 + c * (64 * V) + loff, st[c], lane, n);
+}
+
+// Edge coordinates: one thread each, dword loads, 8 rows in flight.
+template <class Op>
+__device__ __forceinline__ void stream_edges(const float* __restrict__ updates,
+                                             const StreamArgs& a, int64_t e, const Op& op)
+{
+    const int64_t head = a.lo_a - a.lo;
+    const int64_t k = (e < head) ? a.lo + e : a.hi_a + (e - head);
+    if (k >= a.hi_ext)
+        return;
+    if (k >= a.hi) {
+        op.pad_edge(k);
+        return;
+    }
+    typename Op::State st;
+    Op::init(st);
+    const float* p = updates + k;
+    int i = 0;
+    for (; i + 8 <= a.n; i += 8) {
+        float v[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r)
+            v[r] = p[(int64_t)r * a.ld];
+#pragma unroll
+        for (int r = 0; r < 8; ++r)
+            Op::add(st, v[r]);
+        p += 8 * a.ld;
+    }
+    for (; i < a.n; ++i) {
+        Op::add(st, *p);
+        p += a.ld;
+    }
+    op.store_edge(k, st, a.n);
+}
+
+template <class Op, int V, int COLS, int RU, bool NT, bool PIPE>
+__global__ void __launch_bounds__(kBlock)
+stream_kernel(const float* __restrict__ updates, const StreamArgs a, const Op op)
+{
+    if ((int64_t)blockIdx.x < a.edge_blocks) {
+        stream_edges<Op>(updates, a, (int64_t)blockIdx.x * kBlock + threadIdx.x, op);
+        return;
+    }
+    const int64_t b = (int64_t)blockIdx.x - a.edge_blocks;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    constexpr int64_t kSlot = 64 * V;
+    const int64_t slots = (a.hi_a - a.lo_a) / kSlot;
+    // With body_blocks == tiles every block runs one tile.  With fewer (resident) blocks a
+    // block walks tiles b, b + body_blocks, ...
+    for (int64_t t = b; t < a.tiles; t += a.body_blocks) {
+        // Blocks are dealt to the 8 XCDs round-robin.  With the swizzle, XCD x works on the
+        // x-th eighth of the tiles, so neighbouring tiles (which share boundary cache lines
+        // when rows are not line-aligned) meet in the same L2.
+        int64_t tile = t;
+        if (a.swizzle) {
+            const int64_t per = a.tiles / kXcds;       // tiles is a multiple of 8 here
+            tile = (t % kXcds) * per + t / kXcds;
+        }
+        const int64_t s0 = (tile * kWaves + wave) * COLS;
+        if (s0 >= slots)
+            continue;
+        if (s0 + COLS <= slots) {
+            stream_slots<Op, V, COLS, RU, NT, PIPE>(updates, a.ld, a.n, a.lo_a + s0 * kSlot, lane,
+                                                    op);
+        } else {
+            for (int64_t s = s0; s < slots; ++s)   // fewer than COLS slots left at the very end
+                stream_slots<Op, V, 1, RU, NT, PIPE>(updates, a.ld, a.n, a.lo_a + s * kSlot, lane,
+                                                     op);
+        }
+    }
+}
+
+// Kernel lookup by launch tuning; instantiates the whole table for one (Op, V).
+template <class Op>
+using stream_kernel_t = void (*)(const float*, const StreamArgs, const Op);
+
+template <class Op, int V, int COLS, int RU>
+stream_kernel_t<Op> pick_nt(int nt, int pipe)
+{
+    if (pipe)
+        return nt ? stream_kernel<Op, V, COLS, RU, true, true>
+                  : stream_kernel<Op, V, COLS, RU, false, true>;
+    return nt ? stream_kernel<Op, V, COLS, RU, true, false>
+              : stream_kernel<Op, V, COLS, RU, false, false>;
+}
+
+template <class Op, int V, int COLS>
+stream_kernel_t<Op> pick_ru(int ru, int nt, int pipe)
+{
+    switch (ru) {
+    case 2: return pick_nt<Op, V, COLS, 2>(nt, pipe);
+    case 8: return pick_nt<Op, V, COLS, 8>(nt, pipe);
+    default: return pick_nt<Op, V, COLS, 4>(nt, pipe);
+    }
+}
+
+template <class Op, int V>
+stream_kernel_t<Op> pick_cols(int cols, int ru, int nt, int pipe)
+{
+    switch (cols) {
+    case 1: return pick_ru<Op, V, 1>(ru, nt, pipe);
+    case 2: return pick_ru<Op, V, 2>(ru, nt, pipe);
+    case 4: return pick_ru<Op, V, 4>(ru, nt, pipe);
+    default: return pick_ru<Op, V, 8>(ru, nt, pipe);
+    }
+}
+
+}  // namespace brace_dev

@@ -1,8 +1,8 @@
-// Instantiates the streaming vote kernel for 2-dword loads (one translation unit per load
-// width so that the widths compile in parallel).
-#include "vote_kernel.hpp"
+// Instantiates the BRACE vote kernels for 2-dword loads (one translation unit per op and
+// load width so that they compile in parallel).
+#include "ops.hpp"
 
-brace_dev::vote_kernel_t brace_vote_pick_v2(int cols, int ru, int nt, int pipe)
+brace_dev::stream_kernel_t<brace_dev::VoteOp> brace_vote_pick_v2(int cols, int ru, int nt, int pipe)
 {
-    return brace_dev::pick_cols<2>(cols, ru, nt, pipe);
+    return brace_dev::pick_cols<brace_dev::VoteOp, 2>(cols, ru, nt, pipe);
 }

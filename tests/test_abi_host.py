@@ -134,6 +134,31 @@ def test_degenerate_sizes_are_accepted_without_a_launch(L):
     assert _agg(L, n=4, d=0, f=4) == B.BRACE_OK         # f = n is allowed; the rule ignores f
 
 
+def test_rar_aggregate_rejects_invalid_arguments(L):
+    def call(inp=FAKE_IN, n=4, d=100, mean=0, ld=0, out=FAKE_OUT, size=None, chunk=None):
+        p = B.BraceRarParams(ctypes.sizeof(B.BraceRarParams) if size is None else size, mean, ld)
+        if chunk is None:
+            return L.brace_rar_aggregate(inp, n, d, ctypes.byref(p), out, None)
+        return L.brace_rar_aggregate_chunk(inp, n, d, chunk, ctypes.byref(p), out, None)
+    E, R = B.BRACE_EINVAL, B.BRACE_ERANGE
+    assert ctypes.sizeof(B.BraceRarParams) == 16
+    assert L.brace_rar_aggregate(FAKE_IN, 4, 100, None, FAKE_OUT, None) == E
+    assert call(size=8) == E
+    assert call(n=0) == E
+    assert call(n=B.BRACE_MAX_CLIENTS + 1) == R
+    assert call(d=-1) == E
+    assert call(mean=2) == E
+    assert call(ld=50) == E
+    assert call(inp=None) == E
+    assert call(out=None) == E
+    assert call(inp=FAKE_IN + 1) == E
+    assert call(out=FAKE_IN + 40) == E
+    assert call(chunk=4) == R
+    assert call(d=0) == B.BRACE_OK
+    assert call(d=0, inp=None, out=None) == B.BRACE_OK
+    assert call(n=7, d=3, chunk=6) == B.BRACE_OK        # empty chunk, nothing launched
+
+
 def test_tuning_roundtrip_and_validation(L):
     B.brace_reset_tuning()
     base = B.brace_get_tuning()
