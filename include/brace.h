@@ -133,8 +133,8 @@ const char* brace_last_error(void);
 typedef struct brace_tuning {
     uint32_t struct_size;  /* sizeof(brace_tuning_t)                                             */
     int32_t  vec;          /* widest load in dwords: 0 = auto (what alignment allows), 1, 2, 4    */
-    int32_t  cols;         /* loads per lane per row: 1, 2, 4 or 8                                */
-    int32_t  unroll;       /* rows issued before the first is consumed: 2, 4 or 8                 */
+    int32_t  cols;         /* loads per lane per row: 1, 2, 4 or 8; 0 = from the size of the range */
+    int32_t  unroll;       /* rows per batch of loads: 2, 4 or 8; 0 = from the size of the range  */
     int32_t  nontemporal;  /* 1: streaming (non-temporal) loads                                   */
     int32_t  xcd_swizzle;  /* 1: give each of the 8 XCDs a contiguous span of the coordinates     */
     int32_t  persist;      /* 0: one tile per block; k > 0: at most k blocks per compute unit,    */
@@ -142,6 +142,9 @@ typedef struct brace_tuning {
     int32_t  pipeline;     /* 1: request the next batch of rows before consuming the current one  */
     int32_t  split_writes; /* fp32 output written by a second, write-only kernel from the bits:   */
                            /* 0 = for large ranges (default), 1 = never, 2 = whenever possible    */
+    int32_t  rowsplit;     /* the 4 waves of a block share their columns and split the client     */
+                           /* rows (partial results meet in LDS): 0 = for short ranges (default), */
+                           /* 1 = never, 2 = always                                               */
 } brace_tuning_t;
 
 int brace_set_tuning(const brace_tuning_t* tuning);   /* NULL restores the defaults */

@@ -41,6 +41,7 @@ class BraceTuning(ctypes.Structure):
         ("persist", ctypes.c_int32),
         ("pipeline", ctypes.c_int32),
         ("split_writes", ctypes.c_int32),
+        ("rowsplit", ctypes.c_int32),
     ]
 
 
@@ -193,11 +194,11 @@ def brace_aggregate_chunk(updates, f: int, chunk: int, lam: float = 5.0, zero_si
     return out
 
 
-def brace_set_tuning(vec: int = 0, cols: int = 8, unroll: int = 2, nontemporal: int = 1,
+def brace_set_tuning(vec: int = 0, cols: int = 0, unroll: int = 0, nontemporal: int = 1,
                      xcd_swizzle: int = 0, persist: int = 0, pipeline: int = 1,
-                     split_writes: int = 0):
+                     split_writes: int = 0, rowsplit: int = 0):
     t = BraceTuning(ctypes.sizeof(BraceTuning), vec, cols, unroll, nontemporal, xcd_swizzle,
-                    persist, pipeline, split_writes)
+                    persist, pipeline, split_writes, rowsplit)
     _check(lib().brace_set_tuning(ctypes.byref(t)))
 
 

@@ -38,13 +38,14 @@ brace_tuning_t default_tuning()
     brace_tuning_t t;
     t.struct_size = sizeof(brace_tuning_t);
     t.vec = 0;
-    t.cols = 8;
-    t.unroll = 2;
+    t.cols = 0;
+    t.unroll = 0;
     t.nontemporal = 1;
     t.xcd_swizzle = 0;
     t.persist = 0;
     t.pipeline = 1;
     t.split_writes = 0;
+    t.rowsplit = 0;
     return t;
 }
 
@@ -230,10 +231,46 @@ int pick_width(const float* updates, int64_t n, int64_t ld, const void* out4, co
     return v;
 }
 
+// Tile shape of one launch: loads per lane per row, rows per batch, row split.
+struct Shape {
+    int cols, unroll, rowsplit;
+};
+
+// Explicit tuning values win; zeros mean "choose from the size of the range".  Large ranges
+// want long contiguous runs per wave (8 loads per row, 2 rows per batch, double-buffered:
+// 32 KiB in flight per wave at 4-dword loads).  Short ranges shrink the tile until there are
+// about 4 waves per SIMD, and below that split the client rows over the waves of a block.
+Shape choose_shape(const brace_tuning_t& t, int64_t slots, int64_t n)
+{
+    const int64_t cus = compute_units() > 0 ? compute_units() : 256;
+    const int64_t target = 16 * cus;               // 4 SIMDs per CU x 4 waves
+    Shape s;
+    s.cols = t.cols;
+    if (s.cols == 0) {
+        s.cols = 8;
+        while (s.cols > 1 && slots / s.cols < target)
+            s.cols >>= 1;
+    }
+    if (t.rowsplit == 0)
+        s.rowsplit = (n >= 2 * kWaves && slots / s.cols < target / 2) ? 1 : 0;
+    else
+        s.rowsplit = t.rowsplit == 2 ? 1 : 0;
+    if (s.rowsplit && s.cols > kRowsplitMaxCols)
+        s.cols = kRowsplitMaxCols;
+    s.unroll = t.unroll;
+    if (s.unroll == 0) {
+        s.unroll = s.cols >= 8 ? 2 : (s.cols >= 4 ? 4 : 8);
+        const int64_t rows = s.rowsplit ? n / kWaves : n;
+        while (s.unroll > 2 && 2 * s.unroll > rows)
+            s.unroll >>= 1;
+    }
+    return s;
+}
+
 // Geometry of one launch over [lo, hi): body aligned to `unit` coordinates (a multiple of the
 // wave slot 64*v), edges first, optional padding [hi, hi_ext) for the op.  Returns the grid.
-int64_t plan_range(StreamArgs& a, const brace_tuning_t& t, int64_t n, int64_t ld, int v,
-                   int64_t unit, int64_t lo, int64_t hi, int64_t hi_ext)
+int64_t plan_range(StreamArgs& a, Shape& shape, const brace_tuning_t& t, int64_t n, int64_t ld,
+                   int v, int64_t unit, int64_t lo, int64_t hi, int64_t hi_ext)
 {
     a.ld = ld;
     a.n = (int32_t)n;
@@ -249,7 +286,8 @@ int64_t plan_range(StreamArgs& a, const brace_tuning_t& t, int64_t n, int64_t ld
     a.hi_a = hi_a;
 
     const int64_t slots = (hi_a - lo_a) / (64 * (int64_t)v);
-    const int64_t per_block = (int64_t)kWaves * t.cols;
+    shape = choose_shape(t, slots, n);
+    const int64_t per_block = (shape.rowsplit ? 1 : (int64_t)kWaves) * shape.cols;
     int64_t tiles = (slots + per_block - 1) / per_block;
     if (a.swizzle)                 // the swizzled map needs a multiple of 8 tile ids
         tiles = (tiles + kXcds - 1) / kXcds * kXcds;
@@ -305,7 +343,8 @@ int launch_vote(const float* updates, int64_t n, int64_t d, int64_t ld, int thre
     if (bits && hi == d)
         hi_ext = (d + 31) & ~(int64_t)31;          // the last word's padding bits are zeroed
     StreamArgs a;
-    const int64_t grid = plan_range(a, t, n, ld, v, split ? kGroup : 64 * (int64_t)v, lo, hi,
+    Shape sh;
+    const int64_t grid = plan_range(a, sh, t, n, ld, v, split ? kGroup : 64 * (int64_t)v, lo, hi,
                                     hi_ext);
     if (grid <= 0)
         return BRACE_OK;
@@ -315,11 +354,15 @@ int launch_vote(const float* updates, int64_t n, int64_t d, int64_t ld, int thre
 
     stream_kernel_t<VoteOp> k;
     switch (v) {
-    case 4: k = brace_vote_pick_v4(t.cols, t.unroll, t.nontemporal, t.pipeline); break;
-    case 2: k = brace_vote_pick_v2(t.cols, t.unroll, t.nontemporal, t.pipeline); break;
-    default: k = brace_vote_pick_v1(t.cols, t.unroll, t.nontemporal, t.pipeline); break;
+    case 4: k = brace_vote_pick_v4(sh.cols, sh.unroll, t.nontemporal, t.pipeline,
+                                    sh.rowsplit); break;
+    case 2: k = brace_vote_pick_v2(sh.cols, sh.unroll, t.nontemporal, t.pipeline,
+                                    sh.rowsplit); break;
+    default: k = brace_vote_pick_v1(sh.cols, sh.unroll, t.nontemporal, t.pipeline,
+                                    sh.rowsplit); break;
     }
-    hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(kBlock), 0, stream, updates, a, op);
+    const size_t lds = sh.rowsplit ? sizeof(VoteOp::State) * (kWaves - 1) * sh.cols * v * 64 : 0;
+    hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(kBlock), lds, stream, updates, a, op);
     int rc = check_launch("vote kernel");
     if (rc != BRACE_OK)
         return rc;
@@ -343,7 +386,8 @@ int launch_sum(const float* updates, int64_t n, int64_t ld, double scale, float*
     op.out = out;
     op.scale = scale;
     StreamArgs a;
-    const int64_t grid = plan_range(a, t, n, ld, v, 64 * (int64_t)v, lo, hi, hi);
+    Shape sh;
+    const int64_t grid = plan_range(a, sh, t, n, ld, v, 64 * (int64_t)v, lo, hi, hi);
     if (grid <= 0)
         return BRACE_OK;
     if (grid > 0x7fffffffLL)
@@ -351,11 +395,15 @@ int launch_sum(const float* updates, int64_t n, int64_t ld, double scale, float*
                     (long long)grid);
     stream_kernel_t<SumOp> k;
     switch (v) {
-    case 4: k = brace_sum_pick_v4(t.cols, t.unroll, t.nontemporal, t.pipeline); break;
-    case 2: k = brace_sum_pick_v2(t.cols, t.unroll, t.nontemporal, t.pipeline); break;
-    default: k = brace_sum_pick_v1(t.cols, t.unroll, t.nontemporal, t.pipeline); break;
+    case 4: k = brace_sum_pick_v4(sh.cols, sh.unroll, t.nontemporal, t.pipeline,
+                                    sh.rowsplit); break;
+    case 2: k = brace_sum_pick_v2(sh.cols, sh.unroll, t.nontemporal, t.pipeline,
+                                    sh.rowsplit); break;
+    default: k = brace_sum_pick_v1(sh.cols, sh.unroll, t.nontemporal, t.pipeline,
+                                    sh.rowsplit); break;
     }
-    hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(kBlock), 0, stream, updates, a, op);
+    const size_t lds = sh.rowsplit ? sizeof(SumOp::State) * (kWaves - 1) * sh.cols * v * 64 : 0;
+    hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(kBlock), lds, stream, updates, a, op);
     return check_launch("sum kernel");
 }
 
@@ -507,10 +555,13 @@ int brace_set_tuning(const brace_tuning_t* tuning)
         return fail(BRACE_EINVAL, "tuning->struct_size is %u, expected %zu", tuning->struct_size,
                     sizeof(brace_tuning_t));
     const int v = tuning->vec, c = tuning->cols, u = tuning->unroll;
-    if (!(v == 0 || v == 1 || v == 2 || v == 4) || !(c == 1 || c == 2 || c == 4 || c == 8) ||
-        !(u == 2 || u == 4 || u == 8) || tuning->persist < 0 || tuning->persist > 64 ||
-        tuning->split_writes < 0 || tuning->split_writes > 2)
-        return fail(BRACE_EINVAL, "tuning: vec in {0,1,2,4}, cols in {1,2,4,8}, unroll in {2,4,8}, persist in [0,64], split_writes in {0,1,2}");
+    if (!(v == 0 || v == 1 || v == 2 || v == 4) ||
+        !(c == 0 || c == 1 || c == 2 || c == 4 || c == 8) ||
+        !(u == 0 || u == 2 || u == 4 || u == 8) || tuning->persist < 0 || tuning->persist > 64 ||
+        tuning->split_writes < 0 || tuning->split_writes > 2 || tuning->rowsplit < 0 ||
+        tuning->rowsplit > 2)
+        return fail(BRACE_EINVAL, "tuning: vec in {0,1,2,4}, cols in {0,1,2,4,8}, unroll in {0,2,4,8}, persist in "
+                    "[0,64], split_writes and rowsplit in {0,1,2}");
     g_tuning = *tuning;
     return BRACE_OK;
 }

@@ -43,6 +43,12 @@ struct VoteOp {
         s.neg += (v < 0.0f) ? 1 : 0;
     }
 
+    __device__ static __forceinline__ void merge(State& s, const State& o)
+    {
+        s.pos += o.pos;
+        s.neg += o.neg;
+    }
+
     __device__ __forceinline__ int sign_sum(const State& s, int n) const
     {
         return s.pos - s.neg + zero_sign * (n - s.pos - s.neg);
@@ -126,6 +132,7 @@ struct SumOp {
 
     __device__ static __forceinline__ void init(State& s) { s.acc = 0.0; }
     __device__ static __forceinline__ void add(State& s, float v) { s.acc += (double)v; }
+    __device__ static __forceinline__ void merge(State& s, const State& o) { s.acc += o.acc; }
 
     template <int V, bool NT>
     __device__ __forceinline__ void store_body(int64_t k, const State (&st)[V], int, int) const
@@ -149,9 +156,15 @@ struct SumOp {
 }  // namespace brace_dev
 
 // One translation unit per (op, load width) instantiates its share of the kernels.
-brace_dev::stream_kernel_t<brace_dev::VoteOp> brace_vote_pick_v1(int cols, int ru, int nt, int pipe);
-brace_dev::stream_kernel_t<brace_dev::VoteOp> brace_vote_pick_v2(int cols, int ru, int nt, int pipe);
-brace_dev::stream_kernel_t<brace_dev::VoteOp> brace_vote_pick_v4(int cols, int ru, int nt, int pipe);
-brace_dev::stream_kernel_t<brace_dev::SumOp> brace_sum_pick_v1(int cols, int ru, int nt, int pipe);
-brace_dev::stream_kernel_t<brace_dev::SumOp> brace_sum_pick_v2(int cols, int ru, int nt, int pipe);
-brace_dev::stream_kernel_t<brace_dev::SumOp> brace_sum_pick_v4(int cols, int ru, int nt, int pipe);
+brace_dev::stream_kernel_t<brace_dev::VoteOp> brace_vote_pick_v1(int cols, int ru, int nt, int pipe,
+                                                                 int rs);
+brace_dev::stream_kernel_t<brace_dev::VoteOp> brace_vote_pick_v2(int cols, int ru, int nt, int pipe,
+                                                                 int rs);
+brace_dev::stream_kernel_t<brace_dev::VoteOp> brace_vote_pick_v4(int cols, int ru, int nt, int pipe,
+                                                                 int rs);
+brace_dev::stream_kernel_t<brace_dev::SumOp> brace_sum_pick_v1(int cols, int ru, int nt, int pipe,
+                                                                 int rs);
+brace_dev::stream_kernel_t<brace_dev::SumOp> brace_sum_pick_v2(int cols, int ru, int nt, int pipe,
+                                                                 int rs);
+brace_dev::stream_kernel_t<brace_dev::SumOp> brace_sum_pick_v4(int cols, int ru, int nt, int pipe,
+                                                                 int rs);

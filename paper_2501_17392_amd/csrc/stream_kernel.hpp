@@ -19,10 +19,15 @@
 // PIPE the next batch is requested before the current one is consumed, so a wave never
 // drains its outstanding loads between batches.
 //
+// Short ranges (a single ring chunk, small models) do not have enough columns to fill 256
+// compute units with one wave per slot.  In row-split mode the 4 waves of a block share the
+// same slots, each folds a quarter of the client rows, and the partial states meet in LDS.
+//
 // An op provides
 //   struct State;                                  per-coordinate accumulator
 //   static void init(State&);
 //   static void add(State&, float);                fold one client's value
+//   static void merge(State&, const State&);       combine two partial states (row split)
 //   template <int V, bool NT> void store_body(int64_t k, const State (&)[V], int lane, int n) const;
 //                                                  lane's V consecutive coordinates from k
 //   void store_edge(int64_t k, const State&, int n) const;     one coordinate
@@ -97,14 +102,14 @@ struct StreamArgs {
     int64_t tiles;          // tiles in the body; body block b takes tiles b, b + body_blocks, ...
 };
 
-// One wave: COLS adjacent slots starting at wave-uniform coordinate k0.
+// One wave folds rows [0, n) starting at `updates` (already offset to its first row) for
+// COLS adjacent slots starting at wave-uniform coordinate k0.
 template <class Op, int V, int COLS, int RU, bool NT, bool PIPE>
-__device__ __forceinline__ void stream_slots(const float* __restrict__ updates, int64_t ld, int n,
-                                             int64_t k0, int lane, const Op& op)
+__device__ __forceinline__ void stream_accumulate(const float* __restrict__ updates, int64_t ld,
+                                                  int n, int64_t k0, int lane,
+                                                  typename Op::State (&st)[COLS][V])
 {
     typedef typename Vec<V>::type VT;
-    typedef typename Op::State State;
-    State st[COLS][V];
 #pragma unroll
     for (int c = 0; c < COLS; ++c)
 #pragma unroll
@@ -175,10 +180,49 @@ __device__ __forceinline__ void stream_slots(const float* __restrict__ updates, 
                 Op::add(st[c][e], elem<V>(x[c], e));
         row += ld;
     }
+}
 
+// COLS slots from k0: the whole column reduction and its epilogue.  In row-split mode the
+// block's waves each take a contiguous share of the rows; partial states of waves 1.. are
+// parked in LDS (`lds`, (kWaves-1) x COLS*V x 64 states) and wave 0 merges and stores.
+template <class Op, int V, int COLS, int RU, bool NT, bool PIPE, bool RS>
+__device__ __forceinline__ void stream_slots(const float* __restrict__ updates, int64_t ld, int n,
+                                             int64_t k0, int lane, int wave, const Op& op)
+{
+    typedef typename Op::State State;
+    State st[COLS][V];
+    if constexpr (!RS) {
+        stream_accumulate<Op, V, COLS, RU, NT, PIPE>(updates, ld, n, k0, lane, st);
+    } else {
+        extern __shared__ unsigned char lds_raw[];
+        State* lds = reinterpret_cast<State*>(lds_raw);
+        const int r0 = (int)(((int64_t)n * wave) / kWaves);
+        const int r1 = (int)(((int64_t)n * (wave + 1)) / kWaves);
+        stream_accumulate<Op, V, COLS, RU, NT, PIPE>(updates + (int64_t)r0 * ld, ld, r1 - r0, k0,
+                                                     lane, st);
+        if (wave > 0) {
+#pragma unroll
+            for (int c = 0; c < COLS; ++c)
+#pragma unroll
+                for (int e = 0; e < V; ++e)
+                    lds[((wave - 1) * (COLS * V) + c * V + e) * 64 + lane] = st[c][e];
+        }
+        __syncthreads();
+        if (wave == 0) {
+            for (int w = 0; w < kWaves - 1; ++w)
+#pragma unroll
+                for (int c = 0; c < COLS; ++c)
+#pragma unroll
+                    for (int e = 0; e < V; ++e)
+                        Op::merge(st[c][e], lds[(w * (COLS * V) + c * V + e) * 64 + lane]);
+        }
+        __syncthreads();                        // LDS is reused by the block's next tile
+        if (wave > 0)
+            return;
+    }
 #pragma unroll
     for (int c = 0; c < COLS; ++c)
-        op.template store_body<V, NT>(k0 + c * (64 * V) + loff, st[c], lane, n);
+        op.template store_body<V, NT>(k0 + c * (64 * V) + (int64_t)lane * V, st[c], lane, n);
 }
 
 // Edge coordinates: one thread each, dword loads, 8 rows in flight.
@@ -215,7 +259,7 @@ __device__ __forceinline__ void stream_edges(const float* __restrict__ updates,
     op.store_edge(k, st, a.n);
 }
 
-template <class Op, int V, int COLS, int RU, bool NT, bool PIPE>
+template <class Op, int V, int COLS, int RU, bool NT, bool PIPE, bool RS>
 __global__ void __launch_bounds__(kBlock)
 stream_kernel(const float* __restrict__ updates, const StreamArgs a, const Op op)
 {
@@ -239,52 +283,62 @@ stream_kernel(const float* __restrict__ updates, const StreamArgs a, const Op op
             const int64_t per = a.tiles / kXcds;       // tiles is a multiple of 8 here
             tile = (t % kXcds) * per + t / kXcds;
         }
-        const int64_t s0 = (tile * kWaves + wave) * COLS;
+        // Row split: all waves of the block share the tile's COLS slots (block-uniform flow).
+        const int64_t s0 = RS ? tile * COLS : (tile * kWaves + wave) * COLS;
         if (s0 >= slots)
             continue;
         if (s0 + COLS <= slots) {
-            stream_slots<Op, V, COLS, RU, NT, PIPE>(updates, a.ld, a.n, a.lo_a + s0 * kSlot, lane,
-                                                    op);
+            stream_slots<Op, V, COLS, RU, NT, PIPE, RS>(updates, a.ld, a.n, a.lo_a + s0 * kSlot,
+                                                        lane, wave, op);
         } else {
             for (int64_t s = s0; s < slots; ++s)   // fewer than COLS slots left at the very end
-                stream_slots<Op, V, 1, RU, NT, PIPE>(updates, a.ld, a.n, a.lo_a + s * kSlot, lane,
-                                                     op);
+                stream_slots<Op, V, 1, RU, NT, PIPE, RS>(updates, a.ld, a.n, a.lo_a + s * kSlot,
+                                                         lane, wave, op);
         }
     }
 }
 
-// Kernel lookup by launch tuning; instantiates the whole table for one (Op, V).
+// Kernel lookup by launch tuning; instantiates the whole table for one (Op, V).  Row-split
+// kernels exist for 1 and 2 loads per row (short ranges never want more), non-temporal only.
 template <class Op>
 using stream_kernel_t = void (*)(const float*, const StreamArgs, const Op);
 
+constexpr int kRowsplitMaxCols = 2;
+
 template <class Op, int V, int COLS, int RU>
-stream_kernel_t<Op> pick_nt(int nt, int pipe)
+stream_kernel_t<Op> pick_nt(int nt, int pipe, int rs)
 {
+    if constexpr (COLS <= kRowsplitMaxCols) {
+        if (rs)
+            return pipe ? stream_kernel<Op, V, COLS, RU, true, true, true>
+                        : stream_kernel<Op, V, COLS, RU, true, false, true>;
+    }
     if (pipe)
-        return nt ? stream_kernel<Op, V, COLS, RU, true, true>
-                  : stream_kernel<Op, V, COLS, RU, false, true>;
-    return nt ? stream_kernel<Op, V, COLS, RU, true, false>
-              : stream_kernel<Op, V, COLS, RU, false, false>;
+        return nt ? stream_kernel<Op, V, COLS, RU, true, true, false>
+                  : stream_kernel<Op, V, COLS, RU, false, true, false>;
+    return nt ? stream_kernel<Op, V, COLS, RU, true, false, false>
+              : stream_kernel<Op, V, COLS, RU, false, false, false>;
 }
 
 template <class Op, int V, int COLS>
-stream_kernel_t<Op> pick_ru(int ru, int nt, int pipe)
+stream_kernel_t<Op> pick_ru(int ru, int nt, int pipe, int rs)
 {
     switch (ru) {
-    case 2: return pick_nt<Op, V, COLS, 2>(nt, pipe);
-    case 8: return pick_nt<Op, V, COLS, 8>(nt, pipe);
-    default: return pick_nt<Op, V, COLS, 4>(nt, pipe);
+    case 2: return pick_nt<Op, V, COLS, 2>(nt, pipe, rs);
+    case 8: return pick_nt<Op, V, COLS, 8>(nt, pipe, rs);
+    default: return pick_nt<Op, V, COLS, 4>(nt, pipe, rs);
     }
 }
 
+// `cols` must already be <= kRowsplitMaxCols when rs is set.
 template <class Op, int V>
-stream_kernel_t<Op> pick_cols(int cols, int ru, int nt, int pipe)
+stream_kernel_t<Op> pick_cols(int cols, int ru, int nt, int pipe, int rs)
 {
     switch (cols) {
-    case 1: return pick_ru<Op, V, 1>(ru, nt, pipe);
-    case 2: return pick_ru<Op, V, 2>(ru, nt, pipe);
-    case 4: return pick_ru<Op, V, 4>(ru, nt, pipe);
-    default: return pick_ru<Op, V, 8>(ru, nt, pipe);
+    case 1: return pick_ru<Op, V, 1>(ru, nt, pipe, rs);
+    case 2: return pick_ru<Op, V, 2>(ru, nt, pipe, rs);
+    case 4: return pick_ru<Op, V, 4>(ru, nt, pipe, rs);
+    default: return pick_ru<Op, V, 8>(ru, nt, pipe, rs);
     }
 }
 
