@@ -106,6 +106,29 @@ int brace_chunk_range(int64_t n, int64_t d, int64_t chunk, int64_t* lo, int64_t*
 int brace_chunk_owner(int64_t n, int64_t chunk, int64_t* owner_client);
 
 /*
+ * Vote fused with its consumer, the model update of Sec. 2.1 / App. A:
+ *     w[k] <- w[k] - eta * GAR(g_1..g_n)[k]        i.e. every coordinate moves by exactly eta.
+ * w_dev holds d fp32 model parameters, updated in place (one fp32 rounding per coordinate); it
+ * must not overlap updates_dev.  out_bits_dev / sums_dev of params are still produced when
+ * given; when out_bits_dev is given and the range is large, the update itself runs as a
+ * second kernel that reads the bits, which keeps the model's read-modify-write traffic off
+ * the streaming read.  The _chunk form touches w_dev[lo_c .. hi_c) only.
+ */
+int brace_aggregate_update(const float* updates_dev, int64_t n, int64_t d, int64_t f,
+                           const brace_params_t* params, float eta, float* w_dev, void* hip_stream);
+int brace_aggregate_update_chunk(const float* updates_dev, int64_t n, int64_t d, int64_t f,
+                                 int64_t chunk, const brace_params_t* params, float eta,
+                                 float* w_dev, void* hip_stream);
+
+/*
+ * Receive side of the Share-Only phase (Sec. 3 Phase IV): a client that holds the packed
+ * 1-bit result (layout of out_bits_dev, 4*ceil(d/32) bytes) materialises it as d floats of
+ * +-1.0f, or applies it to its model copy as w <- w - eta * (+-1).
+ */
+int brace_expand_bits(const void* bits_dev, int64_t d, float* out_dev, void* hip_stream);
+int brace_apply_bits(const void* bits_dev, int64_t d, float eta, float* w_dev, void* hip_stream);
+
+/*
  * The operation BRACE replaces: plain ring-all-reduce aggregation (Sec. 2.2), out[k] =
  * sum_i updates[i][k], or the Mean rule of Sec. 2.1 (sum / n) with mean = 1.  Same streaming
  * shape and chunking as brace_aggregate.  Accumulation is in fp64 and the result is rounded

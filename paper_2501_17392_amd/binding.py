@@ -66,6 +66,7 @@ EXPORTS = (
     "brace_params_init", "brace_aggregate", "brace_aggregate_chunk", "brace_chunk_range",
     "brace_chunk_owner", "brace_last_error", "brace_set_tuning", "brace_get_tuning",
     "brace_probe_read", "brace_probe_copy", "brace_rar_aggregate", "brace_rar_aggregate_chunk",
+    "brace_aggregate_update", "brace_aggregate_update_chunk", "brace_expand_bits", "brace_apply_bits",
 )
 
 
@@ -107,6 +108,14 @@ def lib():
     L.brace_probe_read.restype = ctypes.c_int
     L.brace_probe_copy.argtypes = [vp, vp, i64, vp]
     L.brace_probe_copy.restype = ctypes.c_int
+    L.brace_aggregate_update.argtypes = [vp, i64, i64, i64, pp, ctypes.c_float, vp, vp]
+    L.brace_aggregate_update.restype = ctypes.c_int
+    L.brace_aggregate_update_chunk.argtypes = [vp, i64, i64, i64, i64, pp, ctypes.c_float, vp, vp]
+    L.brace_aggregate_update_chunk.restype = ctypes.c_int
+    L.brace_expand_bits.argtypes = [vp, i64, vp, vp]
+    L.brace_expand_bits.restype = ctypes.c_int
+    L.brace_apply_bits.argtypes = [vp, i64, ctypes.c_float, vp, vp]
+    L.brace_apply_bits.restype = ctypes.c_int
     rp = ctypes.POINTER(BraceRarParams)
     L.brace_rar_aggregate.argtypes = [vp, i64, i64, rp, vp, vp]
     L.brace_rar_aggregate.restype = ctypes.c_int
@@ -236,3 +245,30 @@ def brace_rar_aggregate(updates, out, mean: bool = False, chunk: int | None = No
         _check(lib().brace_rar_aggregate_chunk(updates.data_ptr(), n, d, chunk, ctypes.byref(p),
                                                _ptr(out), _stream_handle(stream)))
     return out
+
+
+def brace_aggregate_update(updates, f: int, w, eta: float, lam: float = 5.0, zero_sign: int = 0,
+                           out_bits=None, sums=None, chunk: int | None = None, stream=None):
+    """Vote fused with the model update w <- w - eta * result (in place); returns w."""
+    n, d, ld = _matrix(updates)
+    p = make_params(lam, zero_sign, ld, _ptr(out_bits), _ptr(sums))
+    if chunk is None:
+        _check(lib().brace_aggregate_update(updates.data_ptr(), n, d, f, ctypes.byref(p),
+                                            float(eta), _ptr(w), _stream_handle(stream)))
+    else:
+        _check(lib().brace_aggregate_update_chunk(updates.data_ptr(), n, d, f, chunk,
+                                                  ctypes.byref(p), float(eta), _ptr(w),
+                                                  _stream_handle(stream)))
+    return w
+
+
+def brace_expand_bits(bits, d: int, out, stream=None):
+    """Packed result -> d floats of +-1.0f."""
+    _check(lib().brace_expand_bits(_ptr(bits), d, _ptr(out), _stream_handle(stream)))
+    return out
+
+
+def brace_apply_bits(bits, d: int, eta: float, w, stream=None):
+    """Packed result applied to a model copy: w <- w - eta * (+-1)."""
+    _check(lib().brace_apply_bits(_ptr(bits), d, float(eta), _ptr(w), _stream_handle(stream)))
+    return w

@@ -96,6 +96,49 @@ brace_expand_kernel(float* out, const uint32_t* words, int64_t lo_s, int64_t gro
     }
 }
 
+// Same walk over the bit-words, applied to the model instead: w <- w - eta * (+-1).
+__global__ void __launch_bounds__(kBlock)
+brace_apply_kernel(float* __restrict__ w, const uint32_t* __restrict__ words, float eta,
+                   int64_t lo_s, int64_t groups)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int64_t g = (int64_t)blockIdx.x * kWaves + wave;
+    if (g >= groups)
+        return;
+    const int64_t k0 = lo_s + g * kGroup;
+    const uint32_t word = words[(k0 >> 5) + (lane & 31)];
+    f32x4 v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        v[j] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(w + k0 + 256 * j + 4 * lane));
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t ww = (uint32_t)__shfl((int)word, 8 * j + (lane >> 3), 64);
+        const uint32_t nib = ww >> (4 * (lane & 7));
+        v[j][0] -= (nib & 1u) ? eta : -eta;
+        v[j][1] -= (nib & 2u) ? eta : -eta;
+        v[j][2] -= (nib & 4u) ? eta : -eta;
+        v[j][3] -= (nib & 8u) ? eta : -eta;
+        __builtin_nontemporal_store(v[j], reinterpret_cast<f32x4*>(w + k0 + 256 * j + 4 * lane));
+    }
+}
+
+// Coordinates outside whole, aligned groups: one thread each.  out and w may each be null.
+__global__ void __launch_bounds__(kBlock)
+brace_bits_tail_kernel(float* out, float* w, const uint32_t* __restrict__ words, float eta,
+                       int64_t lo, int64_t hi)
+{
+    const int64_t k = lo + (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (k >= hi)
+        return;
+    const bool up = (words[k >> 5] >> (k & 31)) & 1u;
+    if (out)
+        out[k] = up ? 1.0f : -1.0f;
+    if (w)
+        w[k] = w[k] - (up ? eta : -eta);
+}
+
 // ---------------------------------------------------------------------------------------
 // Measurement aids: a plain streaming read and a plain copy of a buffer of known size.
 // They calibrate what the HBM counters report per byte and give the bandwidth a trivially
@@ -313,12 +356,15 @@ int check_launch(const char* what)
 }
 
 int launch_vote(const float* updates, int64_t n, int64_t d, int64_t ld, int thresh,
-                const brace_params_t* p, float* out, int64_t lo, int64_t hi, hipStream_t stream)
+                const brace_params_t* p, float* out, float* w, float eta, int64_t lo, int64_t hi,
+                hipStream_t stream)
 {
     if (hi <= lo)
         return BRACE_OK;
     const brace_tuning_t t = g_tuning;
-    const int v = pick_width(updates, n, ld, out, p->sums_dev, t.vec);
+    int v = pick_width(updates, n, ld, out, p->sums_dev, t.vec);
+    if (w)
+        v = pick_width(updates, n, ld, w, nullptr, v);
     uint32_t* bits = static_cast<uint32_t*>(p->out_bits_dev);
 
     // Split the writes off the read stream?  Needs float output, 16-byte aligned, and whole
@@ -326,7 +372,10 @@ int launch_vote(const float* updates, int64_t n, int64_t d, int64_t ld, int thre
     const int64_t lo_s = (lo + kGroup - 1) / kGroup * kGroup;
     const int64_t hi_s = hi / kGroup * kGroup;
     const int64_t groups = hi_s > lo_s ? (hi_s - lo_s) / kGroup : 0;
-    bool split = out && aligned_to(out, 16) && groups > 0 && t.split_writes != 1;
+    // The fused model update can only be split off when the caller gave a bit array: the
+    // model itself holds live data and cannot park the bit-words.
+    bool split = (out || w) && (!out || aligned_to(out, 16)) && (!w || (bits && aligned_to(w, 16))) &&
+                 groups > 0 && t.split_writes != 1;
     if (split && t.split_writes != 2)
         split = groups >= kSplitMinGroups;
 
@@ -334,10 +383,11 @@ int launch_vote(const float* updates, int64_t n, int64_t d, int64_t ld, int thre
     op.out = out;
     op.bits = bits;
     op.sums = p->sums_dev;
+    op.w = w;
+    op.eta = eta;
     op.thresh = thresh;
     op.zero_sign = p->zero_sign;
     op.split = split ? 1 : 0;
-    op.reserved = 0;
 
     int64_t hi_ext = hi;
     if (bits && hi == d)
@@ -368,9 +418,18 @@ int launch_vote(const float* updates, int64_t n, int64_t d, int64_t ld, int thre
         return rc;
     if (split) {
         const int64_t egrid = (groups + kWaves - 1) / kWaves;
-        hipLaunchKernelGGL(brace_expand_kernel, dim3((unsigned)egrid), dim3(kBlock), 0, stream,
-                           out, static_cast<const uint32_t*>(bits), a.lo_a, groups);
-        rc = check_launch("expand kernel");
+        if (out) {
+            hipLaunchKernelGGL(brace_expand_kernel, dim3((unsigned)egrid), dim3(kBlock), 0, stream,
+                               out, static_cast<const uint32_t*>(bits), a.lo_a, groups);
+            rc = check_launch("expand kernel");
+            if (rc != BRACE_OK)
+                return rc;
+        }
+        if (w) {
+            hipLaunchKernelGGL(brace_apply_kernel, dim3((unsigned)egrid), dim3(kBlock), 0, stream,
+                               w, static_cast<const uint32_t*>(bits), eta, a.lo_a, groups);
+            rc = check_launch("apply kernel");
+        }
     }
     return rc;
 }
@@ -491,8 +550,8 @@ int brace_aggregate(const float* updates_dev, int64_t n, int64_t d, int64_t f,
         return rc;
     // Eq. (1) is per coordinate, so the n chunk aggregations are one pass over [0, d):
     // chunk c's result lands at [lo_c, hi_c) and the chunks tile [0, d).
-    return launch_vote(updates_dev, n, d, ld, thresh, params, out_dev, 0, d,
-                        static_cast<hipStream_t>(hip_stream));
+    return launch_vote(updates_dev, n, d, ld, thresh, params, out_dev, nullptr, 0.0f, 0, d,
+                       static_cast<hipStream_t>(hip_stream));
 }
 
 int brace_aggregate_chunk(const float* updates_dev, int64_t n, int64_t d, int64_t f,
@@ -508,8 +567,110 @@ int brace_aggregate_chunk(const float* updates_dev, int64_t n, int64_t d, int64_
     rc = brace_chunk_range(n, d, chunk, &lo, &hi);
     if (rc != BRACE_OK)
         return rc;
-    return launch_vote(updates_dev, n, d, ld, thresh, params, out_dev, lo, hi,
-                        static_cast<hipStream_t>(hip_stream));
+    return launch_vote(updates_dev, n, d, ld, thresh, params, out_dev, nullptr, 0.0f, lo, hi,
+                       static_cast<hipStream_t>(hip_stream));
+}
+
+// Shared by the fused-update entry points: the vote's validation plus the model buffer.
+static int validate_update(const float* updates, int64_t n, int64_t d, int64_t f,
+                           const brace_params_t* p, float eta, const float* w, int64_t* ld,
+                           int* thresh)
+{
+    // `w` stands in for the float output in the shared checks (non-NULL, aligned, no overlap).
+    const int rc = validate(updates, n, d, f, p, w, ld, thresh);
+    if (rc != BRACE_OK)
+        return rc;
+    if (!std::isfinite(eta))
+        return fail(BRACE_EINVAL, "eta must be finite");
+    if (d > 0 && !w)
+        return fail(BRACE_EINVAL, "w_dev is NULL");
+    return BRACE_OK;
+}
+
+int brace_aggregate_update(const float* updates_dev, int64_t n, int64_t d, int64_t f,
+                           const brace_params_t* params, float eta, float* w_dev, void* hip_stream)
+{
+    int64_t ld;
+    int thresh;
+    const int rc = validate_update(updates_dev, n, d, f, params, eta, w_dev, &ld, &thresh);
+    if (rc != BRACE_OK)
+        return rc;
+    return launch_vote(updates_dev, n, d, ld, thresh, params, nullptr, w_dev, eta, 0, d,
+                       static_cast<hipStream_t>(hip_stream));
+}
+
+int brace_aggregate_update_chunk(const float* updates_dev, int64_t n, int64_t d, int64_t f,
+                                 int64_t chunk, const brace_params_t* params, float eta,
+                                 float* w_dev, void* hip_stream)
+{
+    int64_t ld;
+    int thresh;
+    int rc = validate_update(updates_dev, n, d, f, params, eta, w_dev, &ld, &thresh);
+    if (rc != BRACE_OK)
+        return rc;
+    int64_t lo, hi;
+    rc = brace_chunk_range(n, d, chunk, &lo, &hi);
+    if (rc != BRACE_OK)
+        return rc;
+    return launch_vote(updates_dev, n, d, ld, thresh, params, nullptr, w_dev, eta, lo, hi,
+                       static_cast<hipStream_t>(hip_stream));
+}
+
+// Receive side of Share-Only: a client holding the packed result materialises it.
+static int launch_from_bits(const uint32_t* bits, int64_t d, float* out, float* w, float eta,
+                            hipStream_t stream)
+{
+    if (d == 0)
+        return BRACE_OK;
+    float* target = out ? out : w;
+    const int64_t groups = aligned_to(target, 16) ? d / kGroup : 0;
+    int rc = BRACE_OK;
+    if (groups > 0) {
+        const int64_t egrid = (groups + kWaves - 1) / kWaves;
+        if (egrid > 0x7fffffffLL)
+            return fail(BRACE_ERANGE, "vector too long for one launch");
+        if (out)
+            hipLaunchKernelGGL(brace_expand_kernel, dim3((unsigned)egrid), dim3(kBlock), 0, stream,
+                               out, bits, (int64_t)0, groups);
+        else
+            hipLaunchKernelGGL(brace_apply_kernel, dim3((unsigned)egrid), dim3(kBlock), 0, stream,
+                               w, bits, eta, (int64_t)0, groups);
+        rc = check_launch("bits kernel");
+        if (rc != BRACE_OK)
+            return rc;
+    }
+    const int64_t lo = groups * kGroup;
+    if (lo < d) {
+        const int64_t tgrid = (d - lo + kBlock - 1) / kBlock;
+        if (tgrid > 0x7fffffffLL)
+            return fail(BRACE_ERANGE, "vector too long for one launch");
+        hipLaunchKernelGGL(brace_bits_tail_kernel, dim3((unsigned)tgrid), dim3(kBlock), 0, stream,
+                           out, out ? nullptr : w, bits, eta, lo, d);
+        rc = check_launch("bits tail kernel");
+    }
+    return rc;
+}
+
+int brace_expand_bits(const void* bits_dev, int64_t d, float* out_dev, void* hip_stream)
+{
+    if (d < 0)
+        return fail(BRACE_EINVAL, "d must be >= 0");
+    if (d > 0 && (!bits_dev || !out_dev || !aligned_to(bits_dev, 4) || !aligned_to(out_dev, 4)))
+        return fail(BRACE_EINVAL, "bits_dev and out_dev must be non-NULL and 4-byte aligned");
+    return launch_from_bits(static_cast<const uint32_t*>(bits_dev), d, out_dev, nullptr, 0.0f,
+                            static_cast<hipStream_t>(hip_stream));
+}
+
+int brace_apply_bits(const void* bits_dev, int64_t d, float eta, float* w_dev, void* hip_stream)
+{
+    if (d < 0)
+        return fail(BRACE_EINVAL, "d must be >= 0");
+    if (!std::isfinite(eta))
+        return fail(BRACE_EINVAL, "eta must be finite");
+    if (d > 0 && (!bits_dev || !w_dev || !aligned_to(bits_dev, 4) || !aligned_to(w_dev, 4)))
+        return fail(BRACE_EINVAL, "bits_dev and w_dev must be non-NULL and 4-byte aligned");
+    return launch_from_bits(static_cast<const uint32_t*>(bits_dev), d, nullptr, w_dev, eta,
+                            static_cast<hipStream_t>(hip_stream));
 }
 
 int brace_rar_aggregate(const float* updates_dev, int64_t n, int64_t d,

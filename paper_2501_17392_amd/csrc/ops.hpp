@@ -26,10 +26,11 @@ struct VoteOp {
     float* out;             // d floats, may be null
     uint32_t* bits;         // packed result, may be null
     int16_t* sums;          // sign-sums, may be null
+    float* w;               // model parameters updated in place, may be null
+    float eta;              // learning rate of the fused update w <- w - eta * result
     int32_t thresh;         // result is +1 iff S >= thresh  (thresh = floor(lambda) + 1)
     int32_t zero_sign;      // vote of +-0 and NaN
     int32_t split;          // 1: the body emits bit-words only (a second kernel writes the floats)
-    int32_t reserved;
 
     // Two counters per coordinate: clients voting +1 and clients voting -1.
     struct State { int pos, neg; };
@@ -72,6 +73,15 @@ struct VoteOp {
                 set_elem<V>(o, e, (s[e] >= thresh) ? 1.0f : -1.0f);
             store_vec<NT>(reinterpret_cast<VT*>(out + k), o);
         }
+        if (w && !split) {
+            // Fused consumer of the result (Sec. 2.1; App. A update rule): every coordinate
+            // moves by exactly eta, against the sign of the vote.
+            VT wv = load_vec<V, NT>(w + k);
+#pragma unroll
+            for (int e = 0; e < V; ++e)
+                set_elem<V>(wv, e, elem<V>(wv, e) - ((s[e] >= thresh) ? eta : -eta));
+            store_vec<NT>(reinterpret_cast<VT*>(w + k), wv);
+        }
         if (sums) {
             typedef typename IVec<V>::type ST;
             ST sv;
@@ -104,6 +114,8 @@ struct VoteOp {
         const bool up = s >= thresh;
         if (out)
             out[k] = up ? 1.0f : -1.0f;
+        if (w)
+            w[k] = w[k] - (up ? eta : -eta);
         if (sums)
             sums[k] = (int16_t)s;
         if (bits) {

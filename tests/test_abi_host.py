@@ -134,6 +134,30 @@ def test_degenerate_sizes_are_accepted_without_a_launch(L):
     assert _agg(L, n=4, d=0, f=4) == B.BRACE_OK         # f = n is allowed; the rule ignores f
 
 
+def test_update_and_bits_entry_points_validate(L):
+    E, R = B.BRACE_EINVAL, B.BRACE_ERANGE
+    p = B.make_params()
+    pr = ctypes.byref(p)
+    nan = ctypes.c_float(float("nan"))
+    eta = ctypes.c_float(0.1)
+    assert L.brace_aggregate_update(FAKE_IN, 4, 100, 1, pr, nan, FAKE_OUT, None) == E
+    assert L.brace_aggregate_update(FAKE_IN, 4, 100, 1, pr, eta, None, None) == E
+    assert L.brace_aggregate_update(FAKE_IN, 4, 100, 1, None, eta, FAKE_OUT, None) == E
+    assert L.brace_aggregate_update(FAKE_IN, 4, 100, 1, pr, eta, FAKE_IN + 40, None) == E
+    assert L.brace_aggregate_update(FAKE_IN, 0, 100, 0, pr, eta, FAKE_OUT, None) == E
+    assert L.brace_aggregate_update(FAKE_IN, 4, 0, 1, pr, eta, None, None) == B.BRACE_OK
+    assert L.brace_aggregate_update_chunk(FAKE_IN, 4, 100, 1, 4, pr, eta, FAKE_OUT, None) == R
+    assert L.brace_aggregate_update_chunk(FAKE_IN, 7, 3, 0, 6, pr, eta, FAKE_OUT, None) == B.BRACE_OK
+    assert L.brace_expand_bits(None, 10, FAKE_OUT, None) == E
+    assert L.brace_expand_bits(FAKE_IN, 10, None, None) == E
+    assert L.brace_expand_bits(FAKE_IN + 2, 10, FAKE_OUT, None) == E
+    assert L.brace_expand_bits(FAKE_IN, -1, FAKE_OUT, None) == E
+    assert L.brace_expand_bits(None, 0, None, None) == B.BRACE_OK
+    assert L.brace_apply_bits(FAKE_IN, 10, nan, FAKE_OUT, None) == E
+    assert L.brace_apply_bits(FAKE_IN, 10, eta, None, None) == E
+    assert L.brace_apply_bits(None, 0, eta, None, None) == B.BRACE_OK
+
+
 def test_rar_aggregate_rejects_invalid_arguments(L):
     def call(inp=FAKE_IN, n=4, d=100, mean=0, ld=0, out=FAKE_OUT, size=None, chunk=None):
         p = B.BraceRarParams(ctypes.sizeof(B.BraceRarParams) if size is None else size, mean, ld)

@@ -507,3 +507,22 @@ def test_unmutated_rule_passes_the_same_pins(golden_dir):
     test_special_values_and_zero_sign(rule)
     test_saturating_thresholds(rule)
     test_derived_example_lambda2(rule, golden_dir)
+
+
+# --------------------------------------------------------------------------
+# Model update (Sec. 2.1; App. A update rule w <- w - eta * (2 I - 1))
+# --------------------------------------------------------------------------
+
+def test_model_update_moves_every_coordinate_by_eta():
+    rng = np.random.default_rng(51)
+    n, d, eta, lam = 9, 300, 0.125, 2.0
+    G = _mixed(rng, n, d)
+    w = rng.standard_normal(d)
+    agg = O.brace_direct(G, lam).out
+    new = O.model_update(w, agg, eta)
+    ind = (np.sign(G).sum(0) > lam)                    # the indicator I of App. A
+    assert np.array_equal(new, w - eta * (2.0 * ind - 1.0))
+    assert np.allclose(np.abs(new - w), eta, rtol=0, atol=1e-15)
+    assert (new[ind] < w[ind]).all() and (new[~ind] > w[~ind]).all()
+    # Mean rule plugged into the same update (Sec. 2.1)
+    assert np.allclose(O.model_update(w, O.mean_direct(G), eta), w - eta * G.astype(np.float64).mean(0))
