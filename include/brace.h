@@ -129,6 +129,26 @@ int brace_expand_bits(const void* bits_dev, int64_t d, float* out_dev, void* hip
 int brace_apply_bits(const void* bits_dev, int64_t d, float eta, float* w_dev, void* hip_stream);
 
 /*
+ * Quantise-once form.  brace_quantize is Sec. 3 Phase I kept as data: each client's update
+ * becomes two bit planes ("x > 0", "x < 0"; +-0 and NaN set neither), 2 bits per coordinate.
+ * brace_vote_packed runs Phases II-IV on those planes and gives the same result as
+ * brace_aggregate on the floats, reading 1/16 of the bytes.
+ *
+ * Layout: client i's row at signs_dev + i*ld_words (uint32 words); word pair j of a row is
+ * (positive bits, negative bits) of coordinates 32j .. 32j+31, bit b <-> coordinate 32j+b.
+ * A row has brace_packed_row_words(d) = 2 * roundup(ceil(d/32), 2) words; padding bits are
+ * zero.  ld_words = 0 means exactly that; otherwise a multiple of 4 that is at least that.
+ * signs_dev must be 16-byte aligned.  brace_vote_packed honours lambda, zero_sign and
+ * out_bits_dev of params (params->ld is ignored, sums_dev must be NULL); out_dev must be
+ * 16-byte aligned and may be NULL when out_bits_dev is given.
+ */
+int64_t brace_packed_row_words(int64_t d);
+int brace_quantize(const float* updates_dev, int64_t n, int64_t d, int64_t ld,
+                   uint32_t* signs_dev, int64_t ld_words, void* hip_stream);
+int brace_vote_packed(const uint32_t* signs_dev, int64_t n, int64_t d, int64_t ld_words, int64_t f,
+                      const brace_params_t* params, float* out_dev, void* hip_stream);
+
+/*
  * The operation BRACE replaces: plain ring-all-reduce aggregation (Sec. 2.2), out[k] =
  * sum_i updates[i][k], or the Mean rule of Sec. 2.1 (sum / n) with mean = 1.  Same streaming
  * shape and chunking as brace_aggregate.  Accumulation is in fp64 and the result is rounded

@@ -304,3 +304,50 @@ def mean_direct(updates: np.ndarray) -> np.ndarray:
 def model_update(w: np.ndarray, agg: np.ndarray, eta: float) -> np.ndarray:
     """w <- w - eta * GAR(...) in float64 (Sec. 2.1; App. A update rule)."""
     return np.asarray(w, dtype=np.float64) - float(eta) * np.asarray(agg, dtype=np.float64)
+
+
+# --------------------------------------------------------------------------
+# Quantise-once form: Phase I materialised as bit planes, Phases II-IV on the planes
+# --------------------------------------------------------------------------
+
+def packed_row_words(d: int) -> int:
+    """32-bit words per client row of the packed sign matrix: an even number of
+    (positive, negative) word pairs, so that rows stay 16-byte aligned."""
+    w = (d + 31) // 32
+    w += w & 1
+    return 2 * w
+
+
+def sign_planes(updates: np.ndarray) -> np.ndarray:
+    """Sec. 3 Phase I kept as data: per client two bit planes, "x > 0" and "x < 0".
+
+    Returns uint32 of shape (n, packed_row_words(d)); word pair j = (positive bits,
+    negative bits) of coordinates 32j .. 32j+31, bit b <-> coordinate 32j + b.  A
+    coordinate that is +-0 or NaN has neither bit set; padding bits are zero.
+    """
+    updates = np.asarray(updates)
+    n, d = updates.shape
+    words = packed_row_words(d)
+    out = np.zeros((n, words), dtype=np.uint32)
+    for plane, mask in ((0, updates > 0), (1, updates < 0)):
+        padded = np.zeros((n, (words // 2) * 32), dtype=np.uint8)
+        padded[:, :d] = mask
+        packed = np.packbits(padded, axis=1, bitorder="little")        # bytes, LSB first
+        out[:, plane::2] = packed.view("<u4").reshape(n, words // 2)
+    return out
+
+
+def brace_from_planes(planes: np.ndarray, d: int, lam: float, zero_sign: int = 0) -> BraceResult:
+    """Phases II-IV from the bit planes: S = #pos - #neg + zero_sign * #neither, then Eq. (1)."""
+    planes = np.asarray(planes, dtype=np.uint32)
+    n = planes.shape[0]
+
+    def unpack(plane):
+        words = np.ascontiguousarray(planes[:, plane::2]).astype("<u4")
+        bits = np.unpackbits(words.view(np.uint8).reshape(n, -1), axis=1, bitorder="little")
+        return bits[:, :d].astype(np.int64)
+
+    pos, neg = unpack(0), unpack(1)
+    sums = (pos - neg + zero_sign * (1 - pos - neg)).sum(axis=0)
+    out = consensus(sums, lam)
+    return BraceResult(out=out, sums=sums, bits=pack_bits(out))

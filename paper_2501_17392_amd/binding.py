@@ -67,6 +67,7 @@ EXPORTS = (
     "brace_chunk_owner", "brace_last_error", "brace_set_tuning", "brace_get_tuning",
     "brace_probe_read", "brace_probe_copy", "brace_rar_aggregate", "brace_rar_aggregate_chunk",
     "brace_aggregate_update", "brace_aggregate_update_chunk", "brace_expand_bits", "brace_apply_bits",
+    "brace_packed_row_words", "brace_quantize", "brace_vote_packed",
 )
 
 
@@ -116,6 +117,12 @@ def lib():
     L.brace_expand_bits.restype = ctypes.c_int
     L.brace_apply_bits.argtypes = [vp, i64, ctypes.c_float, vp, vp]
     L.brace_apply_bits.restype = ctypes.c_int
+    L.brace_packed_row_words.argtypes = [i64]
+    L.brace_packed_row_words.restype = ctypes.c_int64
+    L.brace_quantize.argtypes = [vp, i64, i64, i64, vp, i64, vp]
+    L.brace_quantize.restype = ctypes.c_int
+    L.brace_vote_packed.argtypes = [vp, i64, i64, i64, i64, pp, vp, vp]
+    L.brace_vote_packed.restype = ctypes.c_int
     rp = ctypes.POINTER(BraceRarParams)
     L.brace_rar_aggregate.argtypes = [vp, i64, i64, rp, vp, vp]
     L.brace_rar_aggregate.restype = ctypes.c_int
@@ -272,3 +279,27 @@ def brace_apply_bits(bits, d: int, eta: float, w, stream=None):
     """Packed result applied to a model copy: w <- w - eta * (+-1)."""
     _check(lib().brace_apply_bits(_ptr(bits), d, float(eta), _ptr(w), _stream_handle(stream)))
     return w
+
+
+def brace_packed_row_words(d: int) -> int:
+    return int(lib().brace_packed_row_words(d))
+
+
+def brace_quantize(updates, signs, stream=None):
+    """Phase I kept as data: (n, d) floats -> (n, brace_packed_row_words(d)) int32 bit planes."""
+    n, d, ld = _matrix(updates)
+    ld_words = signs.stride(0) if n > 1 else 0
+    _check(lib().brace_quantize(updates.data_ptr(), n, d, ld, signs.data_ptr(), ld_words,
+                                _stream_handle(stream)))
+    return signs
+
+
+def brace_vote_packed(signs, d: int, f: int, lam: float = 5.0, zero_sign: int = 0, out=None,
+                      out_bits=None, stream=None):
+    """Phases II-IV on the packed sign planes; same result as brace_aggregate on the floats."""
+    n = signs.shape[0]
+    ld_words = signs.stride(0) if n > 1 else 0
+    p = make_params(lam, zero_sign, 0, _ptr(out_bits), None)
+    _check(lib().brace_vote_packed(signs.data_ptr(), n, d, ld_words, f, ctypes.byref(p), _ptr(out),
+                                   _stream_handle(stream)))
+    return out

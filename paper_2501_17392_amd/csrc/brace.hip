@@ -13,6 +13,7 @@
 
 #include "brace.h"
 #include "ops.hpp"
+#include "packed.hpp"
 
 namespace {
 
@@ -70,10 +71,11 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // Second phase of a split call: one wave turns the 32 bit-words of a 1024-coordinate group
 // into 1024 floats.  `words` is the linear bit array, or null when the words were parked in
-// the first 128 bytes of the group's own 4 KiB of `out`; the wave reads all 32 words with one
-// load before its first store, so overwriting them is safe.
+// the first 128 bytes of the group's own 4 KiB of `out`; the wave reads all its words with
+// one load before its first store, so overwriting them is safe.  The last group may be cut
+// short at coordinate `hi`.
 __global__ void __launch_bounds__(kBlock)
-brace_expand_kernel(float* out, const uint32_t* words, int64_t lo_s, int64_t groups)
+brace_expand_kernel(float* out, const uint32_t* words, int64_t lo_s, int64_t groups, int64_t hi)
 {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -81,8 +83,9 @@ brace_expand_kernel(float* out, const uint32_t* words, int64_t lo_s, int64_t gro
     if (g >= groups)
         return;
     const int64_t k0 = lo_s + g * kGroup;
+    const int64_t valid = hi - k0 < kGroup ? hi - k0 : kGroup;      // wave-uniform
     const uint32_t* src = words ? words + (k0 >> 5) : reinterpret_cast<const uint32_t*>(out) + k0;
-    const uint32_t w = src[lane & 31];
+    const uint32_t w = ((lane & 31) < (valid + 31) / 32) ? src[lane & 31] : 0u;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const uint32_t ww = (uint32_t)__shfl((int)w, 8 * j + (lane >> 3), 64);
@@ -92,7 +95,14 @@ brace_expand_kernel(float* out, const uint32_t* words, int64_t lo_s, int64_t gro
         o[1] = (nib & 2u) ? 1.0f : -1.0f;
         o[2] = (nib & 4u) ? 1.0f : -1.0f;
         o[3] = (nib & 8u) ? 1.0f : -1.0f;
-        __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(out + k0 + 256 * j + 4 * lane));
+        const int64_t r = 256 * j + 4 * lane;                       // offset inside the group
+        if (r + 4 <= valid) {
+            __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(out + k0 + r));
+        } else {
+            for (int e = 0; e < 4; ++e)
+                if (r + e < valid)
+                    out[k0 + r + e] = o[e];
+        }
     }
 }
 
@@ -420,7 +430,7 @@ int launch_vote(const float* updates, int64_t n, int64_t d, int64_t ld, int thre
         const int64_t egrid = (groups + kWaves - 1) / kWaves;
         if (out) {
             hipLaunchKernelGGL(brace_expand_kernel, dim3((unsigned)egrid), dim3(kBlock), 0, stream,
-                               out, static_cast<const uint32_t*>(bits), a.lo_a, groups);
+                               out, static_cast<const uint32_t*>(bits), a.lo_a, groups, a.hi_a);
             rc = check_launch("expand kernel");
             if (rc != BRACE_OK)
                 return rc;
@@ -631,7 +641,7 @@ static int launch_from_bits(const uint32_t* bits, int64_t d, float* out, float* 
             return fail(BRACE_ERANGE, "vector too long for one launch");
         if (out)
             hipLaunchKernelGGL(brace_expand_kernel, dim3((unsigned)egrid), dim3(kBlock), 0, stream,
-                               out, bits, (int64_t)0, groups);
+                               out, bits, (int64_t)0, groups, groups * kGroup);
         else
             hipLaunchKernelGGL(brace_apply_kernel, dim3((unsigned)egrid), dim3(kBlock), 0, stream,
                                w, bits, eta, (int64_t)0, groups);
@@ -671,6 +681,130 @@ int brace_apply_bits(const void* bits_dev, int64_t d, float eta, float* w_dev, v
         return fail(BRACE_EINVAL, "bits_dev and w_dev must be non-NULL and 4-byte aligned");
     return launch_from_bits(static_cast<const uint32_t*>(bits_dev), d, nullptr, w_dev, eta,
                             static_cast<hipStream_t>(hip_stream));
+}
+
+int64_t brace_packed_row_words(int64_t d)
+{
+    if (d < 0)
+        return 0;
+    int64_t w = (d + 31) / 32;
+    w += w & 1;
+    return 2 * w;
+}
+
+int brace_quantize(const float* updates_dev, int64_t n, int64_t d, int64_t ld,
+                   uint32_t* signs_dev, int64_t ld_words, void* hip_stream)
+{
+    if (n < 1 || d < 0)
+        return fail(BRACE_EINVAL, "need n >= 1 and d >= 0");
+    if (n > BRACE_MAX_CLIENTS)
+        return fail(BRACE_ERANGE, "n = %lld exceeds BRACE_MAX_CLIENTS", (long long)n);
+    if (ld == 0)
+        ld = d;
+    if (ld_words == 0)
+        ld_words = brace_packed_row_words(d);
+    if (ld < d)
+        return fail(BRACE_EINVAL, "ld = %lld is smaller than d = %lld", (long long)ld, (long long)d);
+    if (ld_words < brace_packed_row_words(d) || (ld_words & 3))
+        return fail(BRACE_EINVAL, "ld_words must be a multiple of 4 and >= brace_packed_row_words(d)");
+    if (d == 0)
+        return BRACE_OK;
+    if (!updates_dev || !signs_dev || !aligned_to(updates_dev, 4) || !aligned_to(signs_dev, 16))
+        return fail(BRACE_EINVAL, "updates_dev (4-byte aligned) and signs_dev (16-byte aligned) "
+                                  "must be non-NULL");
+    const int64_t spans = (d + kQuantSpan - 1) / kQuantSpan;
+    const int64_t tasks = spans * n;
+    const int64_t grid = (tasks + kWaves - 1) / kWaves;
+    if (grid > 0x7fffffffLL)
+        return fail(BRACE_ERANGE, "matrix too large for one launch");
+    hipLaunchKernelGGL(brace_quantize_kernel, dim3((unsigned)grid), dim3(kBlock), 0,
+                       static_cast<hipStream_t>(hip_stream), updates_dev, ld, d, signs_dev,
+                       ld_words, spans, tasks);
+    return check_launch("quantize kernel");
+}
+
+int brace_vote_packed(const uint32_t* signs_dev, int64_t n, int64_t d, int64_t ld_words, int64_t f,
+                      const brace_params_t* params, float* out_dev, void* hip_stream)
+{
+    // The scalar checks are those of brace_aggregate; the float matrix is replaced by planes.
+    if (!params)
+        return fail(BRACE_EINVAL, "params is NULL");
+    if (params->struct_size != sizeof(brace_params_t))
+        return fail(BRACE_EINVAL, "params->struct_size is %u, expected %zu", params->struct_size,
+                    sizeof(brace_params_t));
+    if (n < 1 || d < 0 || f < 0 || f > n)
+        return fail(BRACE_EINVAL, "need n >= 1, d >= 0 and 0 <= f <= n");
+    if (n > BRACE_MAX_CLIENTS)
+        return fail(BRACE_ERANGE, "n = %lld exceeds BRACE_MAX_CLIENTS", (long long)n);
+    if (!std::isfinite(params->lambda))
+        return fail(BRACE_EINVAL, "lambda must be finite");
+    if (params->zero_sign < -1 || params->zero_sign > 1 || params->reserved0 != 0)
+        return fail(BRACE_EINVAL, "zero_sign must be -1, 0 or +1 and reserved0 must be 0");
+    if (params->sums_dev)
+        return fail(BRACE_EINVAL, "sign-sums are not produced from packed signs");
+    if (ld_words == 0)
+        ld_words = brace_packed_row_words(d);
+    if (ld_words < brace_packed_row_words(d) || (ld_words & 3))
+        return fail(BRACE_EINVAL, "ld_words must be a multiple of 4 and >= brace_packed_row_words(d)");
+    if (d == 0)
+        return BRACE_OK;
+    uint32_t* bits = static_cast<uint32_t*>(params->out_bits_dev);
+    if (!signs_dev || !aligned_to(signs_dev, 16))
+        return fail(BRACE_EINVAL, "signs_dev must be non-NULL and 16-byte aligned");
+    if (!out_dev && !bits)
+        return fail(BRACE_EINVAL, "no output: out_dev and out_bits_dev are both NULL");
+    if (out_dev && !aligned_to(out_dev, 16))
+        return fail(BRACE_EINVAL, "out_dev must be 16-byte aligned for the packed vote");
+    if (bits && !aligned_to(bits, 4))
+        return fail(BRACE_EINVAL, "out_bits_dev must be 4-byte aligned");
+
+    const double fl = std::floor((double)params->lambda);
+    const int ni = (int)n;
+    int thresh;
+    if (fl >= (double)n)
+        thresh = ni + 1;
+    else if (fl < -(double)n - 1.0)
+        thresh = -ni;
+    else
+        thresh = (int)fl + 1;
+    // S >= thresh as X - Y - c >= 0 on the count slices:
+    //   zero_sign  0: S = P - N            X = P, Y = N, c = thresh
+    //   zero_sign +1: S = n - 2N           N <= floor((n - thresh) / 2)   X = 0, Y = N, c = -M
+    //   zero_sign -1: S = 2P - n           P >= ceil((n + thresh) / 2)    X = P, Y = 0, c = Q
+    uint32_t mask_p = ~0u, mask_n = ~0u;
+    int c = thresh;
+    if (params->zero_sign == 1) {
+        mask_p = 0u;
+        const int num = ni - thresh;
+        c = -(num >= 0 ? num / 2 : -1);
+    } else if (params->zero_sign == -1) {
+        mask_n = 0u;
+        c = (ni + thresh + 1) / 2;
+    }
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int64_t cols4 = brace_packed_row_words(d) / 4;
+    const int64_t grid = (cols4 + kBlock - 1) / kBlock;
+    if (grid > 0x7fffffffLL)
+        return fail(BRACE_ERANGE, "vector too long for one launch");
+    // Bit-words go to the caller's bit array when there is one, else they are parked in out_dev.
+    uint32_t* dst = bits ? bits : reinterpret_cast<uint32_t*>(out_dev);
+    const int scratch = bits ? 0 : 1;
+    const u32x4* planes = reinterpret_cast<const u32x4*>(signs_dev);
+    if (n <= 255)
+        hipLaunchKernelGGL(brace_vote_packed_kernel<8>, dim3((unsigned)grid), dim3(kBlock), 0, stream,
+                           planes, ld_words / 4, ni, cols4, mask_p, mask_n, c, dst, scratch, d);
+    else
+        hipLaunchKernelGGL(brace_vote_packed_kernel<16>, dim3((unsigned)grid), dim3(kBlock), 0, stream,
+                           planes, ld_words / 4, ni, cols4, mask_p, mask_n, c, dst, scratch, d);
+    int rc = check_launch("packed vote kernel");
+    if (rc != BRACE_OK || !out_dev)
+        return rc;
+    const int64_t groups = (d + kGroup - 1) / kGroup;
+    const int64_t egrid = (groups + kWaves - 1) / kWaves;
+    hipLaunchKernelGGL(brace_expand_kernel, dim3((unsigned)egrid), dim3(kBlock), 0, stream, out_dev,
+                       static_cast<const uint32_t*>(bits), (int64_t)0, groups, d);
+    return check_launch("expand kernel");
 }
 
 int brace_rar_aggregate(const float* updates_dev, int64_t n, int64_t d,

@@ -1,0 +1,183 @@
+// Quantise-once form of BRACE for gfx950.
+//
+// Sec. 3 Phase I ("1-bit quantization") kept as data: every client's update becomes two
+// bit planes, "x > 0" and "x < 0" (two planes because +-0 and NaN abstain), 2 bits per
+// coordinate instead of 32.  Phases II-IV then run on the planes: the per-coordinate counts
+// of the n clients are kept bit-sliced (one register per counter bit, 32 coordinates per
+// register), so folding one client's word costs a handful of logic ops for 32 coordinates,
+// and the consensus map of Eq. (1) is evaluated on the slices as well.
+//
+// Layout of the packed matrix: row i (client i) at signs + i*ld_words; word pair j of a row
+// is (positive bits, negative bits) of coordinates 32j .. 32j+31, bit b <-> coordinate 32j+b.
+// Rows hold an even number of pairs (16-byte granularity); padding bits are zero.
+
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "ops.hpp"
+
+namespace brace_dev {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kQuantSpan = 4096;            // coordinates per wave task: 64 loads of 64 lanes
+
+// Phase I for whole rows.  One wave turns 4096 consecutive coordinates of one client into
+// 128 word pairs: a dword load per lane covers 64 coordinates, and the two compares of that
+// load already are the two 64-bit plane masks (one bit per lane).  Lane r keeps the masks
+// of load r, so the wave ends with one 16-byte store per lane, 1 KiB contiguous.
+__global__ void __launch_bounds__(kBlock)
+brace_quantize_kernel(const float* __restrict__ updates, int64_t ld, int64_t d,
+                      uint32_t* __restrict__ signs, int64_t ld_words, int64_t spans_per_row,
+                      int64_t tasks)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int64_t task = (int64_t)blockIdx.x * kWaves + wave;
+    if (task >= tasks)
+        return;
+    const int64_t row = task / spans_per_row;
+    const int64_t k0 = (task % spans_per_row) * kQuantSpan;
+    const float* src = updates + row * ld + k0;
+    const bool full = k0 + kQuantSpan <= d;
+    unsigned long long mine_p = 0, mine_n = 0;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        float x[16];
+        if (full) {
+#pragma unroll
+            for (int u = 0; u < 16; ++u)
+                x[u] = __builtin_nontemporal_load(src + (16 * b + u) * 64 + lane);
+        } else {
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int64_t k = k0 + (16 * b + u) * 64 + lane;
+                x[u] = (k < d) ? src[(16 * b + u) * 64 + lane] : 0.0f;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const unsigned long long mp = __ballot(x[u] > 0.0f);
+            const unsigned long long mn = __ballot(x[u] < 0.0f);
+            if (lane == 16 * b + u) {
+                mine_p = mp;
+                mine_n = mn;
+            }
+        }
+    }
+    const int64_t pair = k0 / 32 + 2 * lane;            // first of this lane's two word pairs
+    if (2 * pair < ld_words && pair < (d + 31) / 32 + (((d + 31) / 32) & 1)) {
+        u32x4 o;
+        o[0] = (uint32_t)mine_p;
+        o[1] = (uint32_t)mine_n;
+        o[2] = (uint32_t)(mine_p >> 32);
+        o[3] = (uint32_t)(mine_n >> 32);
+        *reinterpret_cast<u32x4*>(signs + row * ld_words + 2 * pair) = o;
+    }
+}
+
+// (h, l) <- a + b + c on 32 independent 1-bit lanes per component (carry-save adder).
+__device__ __forceinline__ void csa(u32x4& h, u32x4& l, const u32x4 a, const u32x4 b, const u32x4 c)
+{
+    const u32x4 u = a ^ b;
+    h = (a & b) | (u & c);
+    l = u ^ c;
+}
+
+// Phases II-IV on the planes.  One lane owns two adjacent word pairs (64 coordinates):
+// component 0/1 = positive/negative plane of the first pair, 2/3 of the second.
+// cnt[b] is bit b of the four running counts.  Eight clients are folded at a time through
+// a carry-save tree (ones -> twos -> fours -> eights), and only the "eights" word ripples
+// into the higher counter bits.
+// The decision S >= thresh is taken on the slices as X - Y - c >= 0 with X = pos & mask_p,
+// Y = neg & mask_n and the constant c chosen by the host for the zero_sign in force.
+template <int B>
+__global__ void __launch_bounds__(kBlock)
+brace_vote_packed_kernel(const u32x4* __restrict__ signs, int64_t ld4, int n, int64_t cols4,
+                         uint32_t mask_p, uint32_t mask_n, int c, uint32_t* __restrict__ dst,
+                         int scratch_layout, int64_t d)
+{
+    const int64_t col = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (col >= cols4)
+        return;
+    u32x4 cnt[B];
+#pragma unroll
+    for (int b = 0; b < B; ++b)
+        cnt[b] = (u32x4)(0u);
+
+    const u32x4* p = signs + col;
+    int i = 0;
+    for (; i + 8 <= n; i += 8) {
+        u32x4 a[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r)
+            a[r] = __builtin_nontemporal_load(p + (int64_t)r * ld4);
+        __builtin_amdgcn_sched_barrier(0);
+        u32x4 twos_a, twos_b, fours_a, fours_b, eights;
+        csa(twos_a, cnt[0], cnt[0], a[0], a[1]);
+        csa(twos_b, cnt[0], cnt[0], a[2], a[3]);
+        csa(fours_a, cnt[1], cnt[1], twos_a, twos_b);
+        csa(twos_a, cnt[0], cnt[0], a[4], a[5]);
+        csa(twos_b, cnt[0], cnt[0], a[6], a[7]);
+        csa(fours_b, cnt[1], cnt[1], twos_a, twos_b);
+        csa(eights, cnt[2], cnt[2], fours_a, fours_b);
+        u32x4 carry = eights;
+#pragma unroll
+        for (int b = 3; b < B; ++b) {
+            const u32x4 t = cnt[b] & carry;
+            cnt[b] ^= carry;
+            carry = t;
+        }
+        p += 8 * ld4;
+    }
+    for (; i < n; ++i) {
+        u32x4 carry = *p;
+#pragma unroll
+        for (int b = 0; b < B; ++b) {
+            const u32x4 t = cnt[b] & carry;
+            cnt[b] ^= carry;
+            carry = t;
+        }
+        p += ld4;
+    }
+
+    // Eq. (1) on the slices, for each of the lane's two word pairs.
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        uint32_t diff[B];
+        uint32_t borrow = 0;
+#pragma unroll
+        for (int b = 0; b < B; ++b) {
+            const uint32_t x = cnt[b][2 * h] & mask_p;
+            const uint32_t y = cnt[b][2 * h + 1] & mask_n;
+            const uint32_t u = x ^ y;
+            diff[b] = u ^ borrow;
+            borrow = (~x & y) | (~u & borrow);
+        }
+        const uint32_t sign = borrow;           // all higher bits of X - Y
+        uint32_t borrow2 = 0, top = 0;
+#pragma unroll
+        for (int b = 0; b < B + 2; ++b) {
+            const uint32_t x = (b < B) ? diff[b] : sign;
+            const uint32_t y = ((c >> b) & 1) ? ~0u : 0u;
+            const uint32_t u = x ^ y;
+            top = u ^ borrow2;
+            borrow2 = (~x & y) | (~u & borrow2);
+        }
+        uint32_t result = ~top;                 // bit set <=> X - Y - c >= 0 <=> +1
+        const int64_t k = (2 * col + h) * 32;   // first coordinate of this word
+        if (k >= d)
+            continue;
+        if (d - k < 32)
+            result &= (1u << (d - k)) - 1u;     // padding bits stay zero
+        if (scratch_layout)
+            dst[scratch_word(k)] = result;
+        else
+            dst[k >> 5] = result;
+    }
+}
+
+}  // namespace brace_dev

@@ -158,6 +158,32 @@ def test_update_and_bits_entry_points_validate(L):
     assert L.brace_apply_bits(None, 0, eta, None, None) == B.BRACE_OK
 
 
+def test_packed_entry_points_validate(L):
+    E, R = B.BRACE_EINVAL, B.BRACE_ERANGE
+    for d in (0, 1, 31, 32, 33, 64, 65, 1000, 25_000_000):
+        assert B.brace_packed_row_words(d) == O.packed_row_words(d)
+    p = B.make_params()
+    pr = ctypes.byref(p)
+    assert L.brace_quantize(None, 4, 100, 0, FAKE_OUT, 0, None) == E
+    assert L.brace_quantize(FAKE_IN, 4, 100, 0, None, 0, None) == E
+    assert L.brace_quantize(FAKE_IN, 4, 100, 0, FAKE_OUT + 8, 0, None) == E       # 16-byte rows
+    assert L.brace_quantize(FAKE_IN, 4, 100, 50, FAKE_OUT, 0, None) == E          # ld < d
+    assert L.brace_quantize(FAKE_IN, 4, 100, 0, FAKE_OUT, 4, None) == E           # pitch too small
+    assert L.brace_quantize(FAKE_IN, 4, 100, 0, FAKE_OUT, 10, None) == E          # not a multiple of 4
+    assert L.brace_quantize(FAKE_IN, 0, 100, 0, FAKE_OUT, 0, None) == E
+    assert L.brace_quantize(FAKE_IN, B.BRACE_MAX_CLIENTS + 1, 100, 0, FAKE_OUT, 0, None) == R
+    assert L.brace_quantize(None, 4, 0, 0, None, 0, None) == B.BRACE_OK
+    assert L.brace_vote_packed(FAKE_IN, 4, 100, 0, 1, None, FAKE_OUT, None) == E
+    assert L.brace_vote_packed(None, 4, 100, 0, 1, pr, FAKE_OUT, None) == E
+    assert L.brace_vote_packed(FAKE_IN, 4, 100, 0, 1, pr, None, None) == E          # no output
+    assert L.brace_vote_packed(FAKE_IN, 4, 100, 0, 1, pr, FAKE_OUT + 4, None) == E  # out alignment
+    assert L.brace_vote_packed(FAKE_IN, 4, 100, 6, 1, pr, FAKE_OUT, None) == E
+    assert L.brace_vote_packed(FAKE_IN, 4, 100, 0, 5, pr, FAKE_OUT, None) == E      # f > n
+    with_sums = B.make_params(sums_ptr=FAKE_OUT)
+    assert L.brace_vote_packed(FAKE_IN, 4, 100, 0, 1, ctypes.byref(with_sums), FAKE_OUT, None) == E
+    assert L.brace_vote_packed(None, 4, 0, 0, 1, pr, None, None) == B.BRACE_OK
+
+
 def test_rar_aggregate_rejects_invalid_arguments(L):
     def call(inp=FAKE_IN, n=4, d=100, mean=0, ld=0, out=FAKE_OUT, size=None, chunk=None):
         p = B.BraceRarParams(ctypes.sizeof(B.BraceRarParams) if size is None else size, mean, ld)

@@ -1,0 +1,152 @@
+"""GPU parity for the quantise-once form: Phase I materialised as bit planes (brace_quantize)
+and Phases II-IV on the planes (brace_vote_packed), against the CPU oracle, bit for bit."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import brace_oracle as O
+from oracle import c_oracle as C
+from paper_2501_17392_amd import binding as B
+from paper_2501_17392_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu_and_library():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    B.lib()
+    B.brace_reset_tuning()
+    yield
+
+
+def special(n, d, seed):
+    rng = np.random.default_rng(seed)
+    g = rng.standard_normal((n, d)).astype(np.float32)
+    r = rng.random((n, d))
+    g[r < 0.10] = 0.0
+    g[(r >= 0.10) & (r < 0.13)] = -0.0
+    g[(r >= 0.13) & (r < 0.15)] = np.nan
+    g[(r >= 0.15) & (r < 0.16)] = np.inf
+    g[(r >= 0.16) & (r < 0.17)] = -np.inf
+    g[(r >= 0.17) & (r < 0.19)] = 1e-45
+    g[(r >= 0.19) & (r < 0.21)] = -1e-45
+    return g
+
+
+def to_device(g, ld=None, offset=0):
+    n, d = g.shape
+    ld = d if ld is None else ld
+    store = torch.full((n * max(ld, 1) + offset + 8,), float("nan"), device=DEV, dtype=torch.float32)
+    view = store[offset: offset + n * max(ld, 1)].view(n, max(ld, 1))[:, :d]
+    view.copy_(torch.from_numpy(g))
+    return view
+
+
+def planes_buffer(n, d, extra_words=0):
+    words = B.brace_packed_row_words(d)
+    assert words == O.packed_row_words(d)
+    store = torch.full((n, words + extra_words), -1, device=DEV, dtype=torch.int32)
+    return store[:, :words] if extra_words else store
+
+
+@pytest.mark.parametrize("n,d,ld,offset,extra", [
+    (1, 1, None, 0, 0), (2, 31, None, 0, 0), (3, 32, None, 0, 0), (3, 33, None, 0, 0),
+    (4, 64, None, 0, 0), (5, 1000, None, 0, 0), (3, 4095, None, 0, 0), (3, 4096, None, 0, 0),
+    (3, 4097, None, 0, 0), (7, 12_345, None, 1, 4), (6, 20_000, 20_003, 2, 8), (10, 70_001, None, 0, 0)])
+def test_quantize_matches_oracle_planes(n, d, ld, offset, extra):
+    g = special(n, d, seed=n * 11 + d)
+    upd = to_device(g, ld, offset)
+    signs = planes_buffer(n, d, extra)
+    B.brace_quantize(upd, signs)
+    torch.cuda.synchronize()
+    got = signs.cpu().numpy().view(np.uint32)
+    assert np.array_equal(got, O.sign_planes(g))
+    if extra:       # words past the row are not touched
+        full = signs.untyped_storage()
+        whole = torch.tensor([], dtype=torch.int32, device=DEV).set_(full).view(n, -1).cpu().numpy()
+        assert (whole[:, signs.shape[1]:] == -1).all()
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 7, 8, 9, 15, 16, 17, 100, 255, 256, 300, 1000])
+def test_vote_packed_matches_definition_for_every_client_count(n):
+    d = 2500 if n <= 300 else 700
+    g = special(n, d, seed=n)
+    planes = torch.from_numpy(O.sign_planes(g).view(np.int32)).to(DEV)
+    f = n // 5
+    lams = sorted({-n - 1.0, -1.0, 0.0, 0.5, 2.0, 5.0, float(f), float(n - f), float(n), n - 1.0})
+    for lam in lams:
+        for zs in (0, 1, -1):
+            want = O.brace_direct(g, lam, zs)
+            out = torch.full((d,), 7.0, device=DEV, dtype=torch.float32)
+            bits = torch.full(((d + 31) // 32,), -1, device=DEV, dtype=torch.int32)
+            B.brace_vote_packed(planes, d, f, lam, zs, out=out, out_bits=bits)
+            torch.cuda.synchronize()
+            assert np.array_equal(out.cpu().numpy(), want.out), (n, lam, zs)
+            got_bits = bits.cpu().numpy().view(np.uint8)
+            assert np.array_equal(got_bits[: (d + 7) // 8], want.bits), (n, lam, zs)
+            assert not got_bits[(d + 7) // 8:].any()
+
+
+@pytest.mark.parametrize("d", [1, 31, 32, 33, 1023, 1024, 1025, 2048 + 77, 40_000, 100_003])
+def test_vote_packed_output_variants(d):
+    n = 11
+    g = special(n, d, seed=d)
+    planes = torch.from_numpy(O.sign_planes(g).view(np.int32)).to(DEV)
+    want = O.brace_direct(g, 1.0)
+    guard = torch.full((d + 64,), 3.0, device=DEV, dtype=torch.float32)
+    out = guard[32: 32 + d]
+    B.brace_vote_packed(planes, d, 0, 1.0, out=out)               # floats only: words parked in out
+    torch.cuda.synchronize()
+    gg = guard.cpu().numpy()
+    assert np.array_equal(gg[32: 32 + d], want.out)
+    assert (gg[:32] == 3.0).all() and (gg[32 + d:] == 3.0).all()
+    bits = torch.full(((d + 31) // 32,), -1, device=DEV, dtype=torch.int32)
+    B.brace_vote_packed(planes, d, 0, 1.0, out=None, out_bits=bits)   # bits only
+    torch.cuda.synchronize()
+    assert np.array_equal(bits.cpu().numpy().view(np.uint8)[: (d + 7) // 8], want.bits)
+
+
+def test_quantize_then_vote_equals_float_path_small_workloads():
+    for w in (synth.WORKLOADS[0], synth.WORKLOADS[1]):
+        upd = synth.generate(w, DEV)
+        signs = planes_buffer(w.n, w.d)
+        B.brace_quantize(upd, signs)
+        out = torch.empty(w.d, device=DEV, dtype=torch.float32)
+        B.brace_vote_packed(signs, w.d, w.f, 5.0, out=out)
+        torch.cuda.synchronize()
+        host = upd.cpu().numpy()
+        assert np.array_equal(signs.cpu().numpy().view(np.uint32), O.sign_planes(host))
+        assert np.array_equal(out.cpu().numpy(), O.brace_direct(host, 5.0).out)
+
+
+@pytest.mark.parametrize("idx,col_tile", [(2, 2_000_000), (3, 2_000_000), (4, 4_000_000)])
+def test_large_workloads_full(idx, col_tile):
+    w = synth.WORKLOADS[idx]
+    upd = synth.generate(w, DEV)
+    signs = planes_buffer(w.n, w.d)
+    B.brace_quantize(upd, signs)
+    out = torch.empty(w.d, device=DEV, dtype=torch.float32)
+    bits = torch.empty((w.d + 31) // 32, device=DEV, dtype=torch.int32)
+    B.brace_vote_packed(signs, w.d, w.f, 5.0, out=out, out_bits=bits)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    got_bits = bits.cpu().numpy().view(np.uint8)
+    planes = signs.cpu().numpy().view(np.uint32)
+    for k0 in range(0, w.d, col_tile):
+        k1 = min(w.d, k0 + col_tile)
+        host = upd[:, k0:k1].contiguous().cpu().numpy()
+        want, _, _ = C.brace_direct(host, 5.0, 0, want_sums=False, want_bits=False)
+        assert np.array_equal(got[k0:k1], want), (w.name, k0)
+        assert np.array_equal(got_bits[k0 // 8: (k1 + 7) // 8], O.pack_bits(want)), (w.name, k0)
+        # the planes themselves, on a slice of the tile (the numpy oracle is slow on 1e8 values)
+        s1 = min(k1, k0 + 262_144)
+        ref = O.sign_planes(host[:, : s1 - k0])
+        assert np.array_equal(planes[:, 2 * (k0 // 32): 2 * (k0 // 32) + 2 * ((s1 - k0) // 32)],
+                              ref[:, : 2 * ((s1 - k0) // 32)]), (w.name, k0)
+        print(f"{w.name}: packed vote over columns [{k0}, {k1}) matches", flush=True)
+    del upd, signs
+    torch.cuda.empty_cache()

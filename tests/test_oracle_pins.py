@@ -526,3 +526,32 @@ def test_model_update_moves_every_coordinate_by_eta():
     assert (new[ind] < w[ind]).all() and (new[~ind] > w[~ind]).all()
     # Mean rule plugged into the same update (Sec. 2.1)
     assert np.allclose(O.model_update(w, O.mean_direct(G), eta), w - eta * G.astype(np.float64).mean(0))
+
+
+# --------------------------------------------------------------------------
+# Quantise-once form (Phase I kept as bit planes)
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n,d", [(1, 1), (3, 31), (5, 32), (4, 33), (9, 64), (7, 1000), (20, 4097)])
+def test_planes_route_equals_definition(n, d):
+    rng = np.random.default_rng(n * 100 + d)
+    G = _mixed(rng, n, d)
+    G[rng.random((n, d)) < 0.03] = np.nan
+    planes = O.sign_planes(G)
+    assert planes.shape == (n, O.packed_row_words(d)) and planes.dtype == np.uint32
+    assert O.packed_row_words(d) % 4 == 0
+    assert not (planes[:, 0::2] & planes[:, 1::2]).any()          # never both signs
+    # the planes are exactly "x > 0" and "x < 0", bit b of word j <-> coordinate 32 j + b
+    for i in range(n):
+        for k in rng.integers(0, d, size=min(d, 50)):
+            p = (int(planes[i, 2 * (k // 32)]) >> (k % 32)) & 1
+            m = (int(planes[i, 2 * (k // 32) + 1]) >> (k % 32)) & 1
+            assert p == int(G[i, k] > 0) and m == int(G[i, k] < 0)
+    if d % 32:
+        assert (planes[:, 2 * (d // 32)] >> (d % 32) == 0).all()   # padding bits are zero
+    for lam in (-1, 0, 2):
+        for zs in (-1, 0, 1):
+            a = O.brace_from_planes(planes, d, lam, zs)
+            b = O.brace_direct(G, lam, zs)
+            assert np.array_equal(a.out, b.out) and np.array_equal(a.sums, b.sums)
+            assert np.array_equal(a.bits, b.bits)
