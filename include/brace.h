@@ -53,7 +53,11 @@ typedef struct brace_params {
     float    lambda;       /* threshold of Eq. (1); any finite real.  Sec. 5.1 uses 5.            */
     int32_t  zero_sign;    /* vote cast by +0, -0 and NaN: 0 (default), +1 or -1.  The paper does  */
                            /* not define sign(0); infinities and denormals keep their sign.       */
-    int32_t  reserved0;    /* must be 0                                                           */
+    int32_t  rule;         /* 0: Eq. (1).  1: plain majority sign(S) with ties S = 0 -> 0, i.e.    */
+                           /* signSGD run over the same four phases (Sec. 5.2); lambda is then     */
+                           /* ignored, the result is in {-1, 0, +1} and has no 1-bit form          */
+                           /* (out_bits_dev must be NULL).  Majority with ties -> -1 is rule 0     */
+                           /* with lambda = 0.                                                     */
     int64_t  ld;           /* row pitch of updates_dev in elements; 0 means ld = d                 */
     void*    out_bits_dev; /* optional 1-bit-per-dimension result (the Share-Only wire format of   */
                            /* Sec. 3): bit j of byte b is coordinate 8b+j, 1 <=> +1.  Must be      */

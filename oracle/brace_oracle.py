@@ -351,3 +351,14 @@ def brace_from_planes(planes: np.ndarray, d: int, lam: float, zero_sign: int = 0
     sums = (pos - neg + zero_sign * (1 - pos - neg)).sum(axis=0)
     out = consensus(sums, lam)
     return BraceResult(out=out, sums=sums, bits=pack_bits(out))
+
+
+# --------------------------------------------------------------------------
+# signSGD run over the same four phases (Sec. 5.2): plain majority vote
+# --------------------------------------------------------------------------
+
+def signsgd_majority(updates: np.ndarray, zero_sign: int = 0) -> np.ndarray:
+    """sign(sum_i sign(g_i[k])) in {-1, 0, +1} as float32: Phase III replaced by the plain
+    sign, ties left at 0.  Where the sum is not zero this is Eq. (1) with lambda = 0."""
+    sums = sign_quantize(np.asarray(updates), zero_sign).sum(axis=0, dtype=np.int64)
+    return np.sign(sums).astype(np.float32)

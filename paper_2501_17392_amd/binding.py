@@ -23,7 +23,7 @@ class BraceParams(ctypes.Structure):
         ("struct_size", ctypes.c_uint32),
         ("lambda_", ctypes.c_float),
         ("zero_sign", ctypes.c_int32),
-        ("reserved0", ctypes.c_int32),
+        ("rule", ctypes.c_int32),
         ("ld", ctypes.c_int64),
         ("out_bits_dev", ctypes.c_void_p),
         ("sums_dev", ctypes.c_void_p),
@@ -142,11 +142,13 @@ def _check(rc: int):
 
 
 def make_params(lam: float = 5.0, zero_sign: int = 0, ld: int = 0,
-                out_bits_ptr: int | None = None, sums_ptr: int | None = None) -> BraceParams:
+                out_bits_ptr: int | None = None, sums_ptr: int | None = None,
+                rule: int = 0) -> BraceParams:
     p = BraceParams()
     lib().brace_params_init(ctypes.byref(p))
     p.lambda_ = float(lam)
     p.zero_sign = int(zero_sign)
+    p.rule = int(rule)
     p.ld = int(ld)
     p.out_bits_dev = out_bits_ptr
     p.sums_dev = sums_ptr
@@ -187,24 +189,24 @@ def _matrix(updates):
 
 
 def brace_aggregate(updates, f: int, lam: float = 5.0, zero_sign: int = 0, out=None,
-                    out_bits=None, sums=None, stream=None):
+                    out_bits=None, sums=None, stream=None, rule: int = 0):
     """brace_aggregate of the C ABI on device tensors; returns `out`.
 
     updates: (n, d) float32 device tensor, unit column stride, any row pitch >= d.
     out: float32[d], out_bits: int32/uint8 storage of 4*ceil(d/32) bytes, sums: int16[d].
     """
     n, d, ld = _matrix(updates)
-    p = make_params(lam, zero_sign, ld, _ptr(out_bits), _ptr(sums))
+    p = make_params(lam, zero_sign, ld, _ptr(out_bits), _ptr(sums), rule)
     _check(lib().brace_aggregate(updates.data_ptr(), n, d, f, ctypes.byref(p), _ptr(out),
                                  _stream_handle(stream)))
     return out
 
 
 def brace_aggregate_chunk(updates, f: int, chunk: int, lam: float = 5.0, zero_sign: int = 0,
-                          out=None, out_bits=None, sums=None, stream=None):
+                          out=None, out_bits=None, sums=None, stream=None, rule: int = 0):
     """brace_aggregate_chunk of the C ABI; `out` etc. are the FULL length-d vectors."""
     n, d, ld = _matrix(updates)
-    p = make_params(lam, zero_sign, ld, _ptr(out_bits), _ptr(sums))
+    p = make_params(lam, zero_sign, ld, _ptr(out_bits), _ptr(sums), rule)
     _check(lib().brace_aggregate_chunk(updates.data_ptr(), n, d, f, chunk, ctypes.byref(p),
                                        _ptr(out), _stream_handle(stream)))
     return out
@@ -255,10 +257,11 @@ def brace_rar_aggregate(updates, out, mean: bool = False, chunk: int | None = No
 
 
 def brace_aggregate_update(updates, f: int, w, eta: float, lam: float = 5.0, zero_sign: int = 0,
-                           out_bits=None, sums=None, chunk: int | None = None, stream=None):
+                           out_bits=None, sums=None, chunk: int | None = None, stream=None,
+                           rule: int = 0):
     """Vote fused with the model update w <- w - eta * result (in place); returns w."""
     n, d, ld = _matrix(updates)
-    p = make_params(lam, zero_sign, ld, _ptr(out_bits), _ptr(sums))
+    p = make_params(lam, zero_sign, ld, _ptr(out_bits), _ptr(sums), rule)
     if chunk is None:
         _check(lib().brace_aggregate_update(updates.data_ptr(), n, d, f, ctypes.byref(p),
                                             float(eta), _ptr(w), _stream_handle(stream)))

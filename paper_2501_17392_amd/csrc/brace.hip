@@ -227,8 +227,10 @@ int validate(const float* updates, int64_t n, int64_t d, int64_t f, const brace_
         return fail(BRACE_EINVAL, "lambda must be finite");
     if (p->zero_sign < -1 || p->zero_sign > 1)
         return fail(BRACE_EINVAL, "zero_sign must be -1, 0 or +1");
-    if (p->reserved0 != 0)
-        return fail(BRACE_EINVAL, "reserved0 must be 0");
+    if (p->rule != 0 && p->rule != 1)
+        return fail(BRACE_EINVAL, "rule must be 0 (Eq. (1)) or 1 (majority sign)");
+    if (p->rule == 1 && p->out_bits_dev)
+        return fail(BRACE_EINVAL, "the majority rule is three-valued and has no 1-bit form");
     if (p->ld != 0 && p->ld < d)
         return fail(BRACE_EINVAL, "ld = %lld is smaller than d = %lld", (long long)p->ld,
                     (long long)d);
@@ -261,6 +263,8 @@ int validate(const float* updates, int64_t n, int64_t d, int64_t f, const brace_
         t = -(int)n;               // always reached: all +1
     else
         t = (int)fl + 1;
+    if (p->rule == 1)
+        t = 1;                     // sign(S): +1 iff S >= 1, 0 at S == 0 (set by the kernel)
     *thresh_out = t;
     return BRACE_OK;
 }
@@ -388,6 +392,8 @@ int launch_vote(const float* updates, int64_t n, int64_t d, int64_t ld, int thre
                  groups > 0 && t.split_writes != 1;
     if (split && t.split_writes != 2)
         split = groups >= kSplitMinGroups;
+    if (p->rule == 1)
+        split = false;             // three values do not fit the bit-words
 
     VoteOp op;
     op.out = out;
@@ -398,6 +404,7 @@ int launch_vote(const float* updates, int64_t n, int64_t d, int64_t ld, int thre
     op.thresh = thresh;
     op.zero_sign = p->zero_sign;
     op.split = split ? 1 : 0;
+    op.tie_zero = p->rule == 1 ? 1 : 0;
 
     int64_t hi_ext = hi;
     if (bits && hi == d)
@@ -738,8 +745,9 @@ int brace_vote_packed(const uint32_t* signs_dev, int64_t n, int64_t d, int64_t l
         return fail(BRACE_ERANGE, "n = %lld exceeds BRACE_MAX_CLIENTS", (long long)n);
     if (!std::isfinite(params->lambda))
         return fail(BRACE_EINVAL, "lambda must be finite");
-    if (params->zero_sign < -1 || params->zero_sign > 1 || params->reserved0 != 0)
-        return fail(BRACE_EINVAL, "zero_sign must be -1, 0 or +1 and reserved0 must be 0");
+    if (params->zero_sign < -1 || params->zero_sign > 1 || params->rule != 0)
+        return fail(BRACE_EINVAL, "zero_sign must be -1, 0 or +1; the packed vote implements "
+                                  "rule 0 only");
     if (params->sums_dev)
         return fail(BRACE_EINVAL, "sign-sums are not produced from packed signs");
     if (ld_words == 0)

@@ -31,6 +31,7 @@ struct VoteOp {
     int32_t thresh;         // result is +1 iff S >= thresh  (thresh = floor(lambda) + 1)
     int32_t zero_sign;      // vote of +-0 and NaN
     int32_t split;          // 1: the body emits bit-words only (a second kernel writes the floats)
+    int32_t tie_zero;       // 1: majority rule, S == 0 gives 0 (thresh is 1 then)
 
     // Two counters per coordinate: clients voting +1 and clients voting -1.
     struct State { int pos, neg; };
@@ -48,6 +49,13 @@ struct VoteOp {
     {
         s.pos += o.pos;
         s.neg += o.neg;
+    }
+
+    // Phase III: Eq. (1), or the three-valued majority sign.
+    __device__ __forceinline__ float decide(int s) const
+    {
+        const float v = (s >= thresh) ? 1.0f : -1.0f;
+        return (tie_zero && s == 0) ? 0.0f : v;
     }
 
     __device__ __forceinline__ int sign_sum(const State& s, int n) const
@@ -70,7 +78,7 @@ struct VoteOp {
             VT o;
 #pragma unroll
             for (int e = 0; e < V; ++e)
-                set_elem<V>(o, e, (s[e] >= thresh) ? 1.0f : -1.0f);
+                set_elem<V>(o, e, decide(s[e]));
             store_vec<NT>(reinterpret_cast<VT*>(out + k), o);
         }
         if (w && !split) {
@@ -79,7 +87,7 @@ struct VoteOp {
             VT wv = load_vec<V, NT>(w + k);
 #pragma unroll
             for (int e = 0; e < V; ++e)
-                set_elem<V>(wv, e, elem<V>(wv, e) - ((s[e] >= thresh) ? eta : -eta));
+                set_elem<V>(wv, e, elem<V>(wv, e) - eta * decide(s[e]));
             store_vec<NT>(reinterpret_cast<VT*>(w + k), wv);
         }
         if (sums) {
@@ -113,9 +121,9 @@ struct VoteOp {
         const int s = sign_sum(st, n);
         const bool up = s >= thresh;
         if (out)
-            out[k] = up ? 1.0f : -1.0f;
+            out[k] = decide(s);
         if (w)
-            w[k] = w[k] - (up ? eta : -eta);
+            w[k] = w[k] - eta * decide(s);
         if (sums)
             sums[k] = (int16_t)s;
         if (bits) {

@@ -118,9 +118,9 @@ def test_aggregate_rejects_invalid_arguments_before_touching_the_gpu(L):
     bad.struct_size = 12
     assert _agg(L, p=bad) == E
     assert "struct_size" in B.brace_last_error()
-    bad = B.make_params()
-    bad.reserved0 = 1
-    assert _agg(L, p=bad) == E
+    assert _agg(L, rule=2) == E
+    assert _agg(L, rule=-1) == E
+    assert _agg(L, rule=1, out_bits_ptr=FAKE_OUT + 0x1000) == E   # no 1-bit form of {-1, 0, +1}
     assert _agg(L, chunk=4) == R
     assert _agg(L, chunk=-1) == R
     assert "chunk" in B.brace_last_error()

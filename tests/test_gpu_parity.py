@@ -152,6 +152,37 @@ def test_padding_never_leaks_into_the_result():
     assert np.array_equal(g[32: 32 + d], O.brace_direct(upd.cpu().numpy(), 0.0).out)
 
 
+def test_majority_rule_three_valued():
+    # signSGD's plain majority over the same four phases: ties stay at 0.
+    for n, d in ((4, 5000), (7, 3001), (10, 70_001)):
+        upd = special_matrix(n, d, seed=n)
+        host = upd.cpu().numpy()
+        for zs in (0, 1, -1):
+            want = O.signsgd_majority(host, zs)
+            out = torch.full((d,), 7.0, device=DEV, dtype=torch.float32)
+            sums = torch.zeros(d, device=DEV, dtype=torch.int16)
+            B.brace_aggregate(upd, 0, 123.0, zs, out=out, sums=sums, rule=1)   # lambda is ignored
+            torch.cuda.synchronize()
+            assert np.array_equal(out.cpu().numpy(), want), (n, d, zs)
+            assert np.array_equal(sums.cpu().numpy().astype(np.int64), O.brace_direct(host, 0.0, zs).sums)
+            parts = torch.full((d,), 7.0, device=DEV, dtype=torch.float32)
+            for c in range(n):
+                B.brace_aggregate_chunk(upd, 0, c, 0.0, zs, out=parts, rule=1)
+            torch.cuda.synchronize()
+            assert np.array_equal(parts.cpu().numpy(), want)
+        if n == 4:
+            assert (want == 0).any()
+        w0 = torch.randn(d, device=DEV)
+        w = w0.clone()
+        B.brace_aggregate_update(upd, 0, w, 0.5, 0.0, rule=1)
+        torch.cuda.synchronize()
+        want_w = O.model_update(w0.cpu().numpy(), O.signsgd_majority(host), 0.5)
+        assert np.allclose(w.cpu().numpy(), want_w, rtol=1e-5, atol=1e-6)
+    with pytest.raises(B.BraceError):
+        B.brace_aggregate(upd, 0, 0.0, out=out, out_bits=torch.zeros(4000, device=DEV, dtype=torch.int32),
+                          rule=1)
+
+
 # --------------------------------------------------------------------------
 # Per-chunk entry point: union of the chunks == whole, byte for byte
 # --------------------------------------------------------------------------

@@ -555,3 +555,22 @@ def test_planes_route_equals_definition(n, d):
             b = O.brace_direct(G, lam, zs)
             assert np.array_equal(a.out, b.out) and np.array_equal(a.sums, b.sums)
             assert np.array_equal(a.bits, b.bits)
+
+
+# --------------------------------------------------------------------------
+# signSGD majority vote over the same phases (Sec. 5.2)
+# --------------------------------------------------------------------------
+
+def test_majority_rule_relation_to_eq_1():
+    rng = np.random.default_rng(61)
+    for n in (4, 7, 10):
+        G = _mixed(rng, n, 400)
+        maj = O.signsgd_majority(G)
+        S = O.brace_direct(G, 0.0).sums
+        assert set(np.unique(maj)) <= {-1.0, 0.0, 1.0}
+        assert np.array_equal(maj == 0, S == 0)
+        brace0 = O.brace_direct(G, 0.0).out          # lambda = 0: ties go to -1
+        assert np.array_equal(maj[S != 0], brace0[S != 0])
+        assert (brace0[S == 0] == -1).all()
+    G = rng.standard_normal((9, 300)).astype(np.float32)      # odd n, no zeros: median sign
+    assert np.array_equal(O.signsgd_majority(G), np.sign(np.median(G, axis=0)).astype(np.float32))
