@@ -86,9 +86,11 @@ def main():
     ap.add_argument("--lam", type=float, default=5.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-cols", type=int, default=25_000_000)
-    ap.add_argument("--probe", action="store_true",
-                    help="also run the plain read / copy kernels on 1 GiB (counter calibration "
-                         "and linear-access bandwidth); reported under 'probe'")
+    ap.add_argument("--no-probe", dest="probe", action="store_false",
+                    help="skip the plain read / copy kernels on 1 GiB (counter calibration and "
+                         "linear-access bandwidth, reported under 'probe')")
+    ap.add_argument("--probe", dest="probe", action="store_true", help=argparse.SUPPRESS)
+    ap.set_defaults(probe=True)
     ap.add_argument("--tuning", default="",
                     help="vec,cols,unroll,nontemporal,xcd_swizzle (default: library defaults)")
     args = ap.parse_args()

@@ -96,6 +96,15 @@ int brace_aggregate_chunk(const float* updates_dev, int64_t n, int64_t d, int64_
                           void* hip_stream);
 
 /*
+ * A run of consecutive ring chunks [chunk_begin, chunk_end) in one launch -- the share of one
+ * device when the coordinate axis is split over several.  Same contract as the single-chunk
+ * form; an empty run is a no-op.
+ */
+int brace_aggregate_chunks(const float* updates_dev, int64_t n, int64_t d, int64_t f,
+                           int64_t chunk_begin, int64_t chunk_end, const brace_params_t* params,
+                           float* out_dev, void* hip_stream);
+
+/*
  * Chunk partition (Sec. 2.2: "n roughly equal-sized sub-vectors").  Contiguous, ascending;
  * with q = d div n, r = d mod n the first r chunks have q+1 coordinates, the rest q.
  * Host arithmetic only.  [lo, hi) is half-open.

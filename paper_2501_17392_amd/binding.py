@@ -67,7 +67,7 @@ EXPORTS = (
     "brace_chunk_owner", "brace_last_error", "brace_set_tuning", "brace_get_tuning",
     "brace_probe_read", "brace_probe_copy", "brace_rar_aggregate", "brace_rar_aggregate_chunk",
     "brace_aggregate_update", "brace_aggregate_update_chunk", "brace_expand_bits", "brace_apply_bits",
-    "brace_packed_row_words", "brace_quantize", "brace_vote_packed",
+    "brace_packed_row_words", "brace_quantize", "brace_vote_packed", "brace_aggregate_chunks",
 )
 
 
@@ -95,6 +95,8 @@ def lib():
     L.brace_aggregate.restype = ctypes.c_int
     L.brace_aggregate_chunk.argtypes = [vp, i64, i64, i64, i64, pp, vp, vp]
     L.brace_aggregate_chunk.restype = ctypes.c_int
+    L.brace_aggregate_chunks.argtypes = [vp, i64, i64, i64, i64, i64, pp, vp, vp]
+    L.brace_aggregate_chunks.restype = ctypes.c_int
     L.brace_chunk_range.argtypes = [i64, i64, i64, ctypes.POINTER(i64), ctypes.POINTER(i64)]
     L.brace_chunk_range.restype = ctypes.c_int
     L.brace_chunk_owner.argtypes = [i64, i64, ctypes.POINTER(i64)]
@@ -305,4 +307,14 @@ def brace_vote_packed(signs, d: int, f: int, lam: float = 5.0, zero_sign: int = 
     p = make_params(lam, zero_sign, 0, _ptr(out_bits), None)
     _check(lib().brace_vote_packed(signs.data_ptr(), n, d, ld_words, f, ctypes.byref(p), _ptr(out),
                                    _stream_handle(stream)))
+    return out
+
+
+def brace_aggregate_chunks(updates, f: int, chunk_begin: int, chunk_end: int, lam: float = 5.0,
+                           zero_sign: int = 0, out=None, out_bits=None, sums=None, stream=None):
+    """A run of consecutive ring chunks in one launch; `out` etc. are the FULL vectors."""
+    n, d, ld = _matrix(updates)
+    p = make_params(lam, zero_sign, ld, _ptr(out_bits), _ptr(sums))
+    _check(lib().brace_aggregate_chunks(updates.data_ptr(), n, d, f, chunk_begin, chunk_end,
+                                        ctypes.byref(p), _ptr(out), _stream_handle(stream)))
     return out

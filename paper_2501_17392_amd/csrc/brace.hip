@@ -588,6 +588,32 @@ int brace_aggregate_chunk(const float* updates_dev, int64_t n, int64_t d, int64_
                        static_cast<hipStream_t>(hip_stream));
 }
 
+int brace_aggregate_chunks(const float* updates_dev, int64_t n, int64_t d, int64_t f,
+                           int64_t chunk_begin, int64_t chunk_end, const brace_params_t* params,
+                           float* out_dev, void* hip_stream)
+{
+    int64_t ld;
+    int thresh;
+    int rc = validate(updates_dev, n, d, f, params, out_dev, &ld, &thresh);
+    if (rc != BRACE_OK)
+        return rc;
+    if (chunk_begin < 0 || chunk_end > n || chunk_begin > chunk_end)
+        return fail(BRACE_ERANGE, "chunk range [%lld, %lld) outside [0, %lld]",
+                    (long long)chunk_begin, (long long)chunk_end, (long long)n);
+    if (chunk_begin == chunk_end)
+        return BRACE_OK;
+    int64_t lo, hi, unused;
+    rc = brace_chunk_range(n, d, chunk_begin, &lo, &unused);
+    if (rc != BRACE_OK)
+        return rc;
+    rc = brace_chunk_range(n, d, chunk_end - 1, &unused, &hi);
+    if (rc != BRACE_OK)
+        return rc;
+    // consecutive chunks are contiguous, so a run of chunks is one coordinate range
+    return launch_vote(updates_dev, n, d, ld, thresh, params, out_dev, nullptr, 0.0f, lo, hi,
+                       static_cast<hipStream_t>(hip_stream));
+}
+
 // Shared by the fused-update entry points: the vote's validation plus the model buffer.
 static int validate_update(const float* updates, int64_t n, int64_t d, int64_t f,
                            const brace_params_t* p, float eta, const float* w, int64_t* ld,

@@ -126,6 +126,18 @@ def test_aggregate_rejects_invalid_arguments_before_touching_the_gpu(L):
     assert "chunk" in B.brace_last_error()
 
 
+def test_chunk_run_validation(L):
+    p = B.make_params()
+    pr = ctypes.byref(p)
+    R = B.BRACE_ERANGE
+    assert L.brace_aggregate_chunks(FAKE_IN, 4, 100, 1, -1, 2, pr, FAKE_OUT, None) == R
+    assert L.brace_aggregate_chunks(FAKE_IN, 4, 100, 1, 0, 5, pr, FAKE_OUT, None) == R
+    assert L.brace_aggregate_chunks(FAKE_IN, 4, 100, 1, 3, 2, pr, FAKE_OUT, None) == R
+    assert L.brace_aggregate_chunks(FAKE_IN, 4, 100, 1, 2, 2, pr, FAKE_OUT, None) == B.BRACE_OK
+    assert L.brace_aggregate_chunks(FAKE_IN, 7, 3, 0, 4, 7, pr, FAKE_OUT, None) == B.BRACE_OK  # empty chunks
+    assert L.brace_aggregate_chunks(None, 4, 100, 1, 0, 2, pr, FAKE_OUT, None) == B.BRACE_EINVAL
+
+
 def test_degenerate_sizes_are_accepted_without_a_launch(L):
     assert _agg(L, d=0) == B.BRACE_OK                   # nothing to do
     assert _agg(L, d=0, inp=None, out=None) == B.BRACE_OK  # empty buffers may be NULL

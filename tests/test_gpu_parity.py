@@ -213,6 +213,30 @@ def test_chunks_tile_the_whole(n, d):
     assert np.array_equal(whole[0], want.out)
 
 
+def test_runs_of_chunks_tile_the_whole():
+    # eight "devices" each taking a run of consecutive chunks
+    n, d = 100, 250_007
+    upd = special_matrix(n, d, seed=12)
+    want = O.brace_direct(upd.cpu().numpy(), 2.0)
+    out = torch.full((d,), 7.0, device=DEV, dtype=torch.float32)
+    bits = torch.full(((d + 31) // 32,), -1, device=DEV, dtype=torch.int32)
+    sums = torch.full((d,), 12345, device=DEV, dtype=torch.int16)
+    cuts = [0, 13, 25, 38, 50, 63, 75, 88, 100]
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        B.brace_aggregate_chunks(upd, 20, a, b, 2.0, out=out, out_bits=bits, sums=sums)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), want.out)
+    assert np.array_equal(sums.cpu().numpy().astype(np.int64), want.sums)
+    assert np.array_equal(bits.cpu().numpy().view(np.uint8)[: (d + 7) // 8], want.bits)
+    lo, _ = B.brace_chunk_range(n, d, 13)
+    _, hi = B.brace_chunk_range(n, d, 24)
+    part = torch.full((d,), 7.0, device=DEV, dtype=torch.float32)
+    B.brace_aggregate_chunks(upd, 20, 13, 25, 2.0, out=part)
+    torch.cuda.synchronize()
+    p = part.cpu().numpy()
+    assert np.array_equal(p[lo:hi], want.out[lo:hi]) and (p[:lo] == 7).all() and (p[hi:] == 7).all()
+
+
 def test_single_chunk_touches_only_its_range():
     n, d, c = 10, 10_007, 4
     upd = special_matrix(n, d, seed=3)
