@@ -269,17 +269,21 @@ int validate(const float* updates, int64_t n, int64_t d, int64_t f, const brace_
     return BRACE_OK;
 }
 
-// Widest load (in dwords) that the matrix and every vector store of `bytes_per_coord`-sized
-// outputs can use, capped by the tuning.
+// Access width (in dwords) for one launch.  Vector stores need natural alignment: 4-byte
+// outputs at out4, 2-byte outputs at out2.  Loads of the matrix only need dword alignment
+// (see load_vec); measured on cfg 1 / cfg 2: rows that are 8-byte aligned run best with
+// aligned 2-dword loads (6.96 vs 6.5 TB/s with misaligned 4-dword loads), rows that are only
+// 4-byte aligned run best with misaligned 4-dword loads (14.2 vs 17.6 us with dword loads).
+// `cap` (tuning) can only narrow the result.
 int pick_width(const float* updates, int64_t n, int64_t ld, const void* out4, const void* out2,
                int cap)
 {
-    int v = 4;
+    int rows = 4;                   // widest load that is aligned in every row
+    while (rows > 1 && !(aligned_to(updates, 4u * rows) && (ld % rows == 0 || n == 1)))
+        rows >>= 1;
+    int v = rows == 1 ? 4 : rows;
     while (v > 1) {
-        const uintptr_t bytes = 4u * v;
-        const bool ok = aligned_to(updates, bytes) && (ld % v == 0 || n == 1) &&
-                        (!out4 || aligned_to(out4, bytes)) && (!out2 || aligned_to(out2, 2u * v));
-        if (ok)
+        if ((!out4 || aligned_to(out4, 4u * v)) && (!out2 || aligned_to(out2, 2u * v)))
             break;
         v >>= 1;
     }

@@ -70,14 +70,18 @@ __device__ __forceinline__ void set_elem(typename Vec<V>::type& v, int e, float 
     if constexpr (V == 1) v = x; else v[e] = x;
 }
 
+// Row loads only promise 4-byte alignment: with a pitch that is not a multiple of 4 elements
+// every client row has its own 16-byte phase, and gfx950 global loads of 2 or 4 dwords do not
+// need more than dword alignment.  Aligned rows get the same instruction.
 template <int V, bool NT>
 __device__ __forceinline__ typename Vec<V>::type load_vec(const float* p)
 {
     typedef typename Vec<V>::type T;
+    typedef T TU __attribute__((aligned(4)));
     if constexpr (NT)
-        return __builtin_nontemporal_load(reinterpret_cast<const T*>(p));
+        return __builtin_nontemporal_load(reinterpret_cast<const TU*>(p));
     else
-        return *reinterpret_cast<const T*>(p);
+        return *reinterpret_cast<const TU*>(p);
 }
 
 template <bool NT, typename T>
