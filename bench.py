@@ -26,8 +26,8 @@ HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published peak
 # dispatch, scaled by the same counters' reading for a copy kernel of known size).
 # Filled from the summaries kept under profiles/; None = not measured for that workload.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/brace_vote_kernel_cfg3_n100_d25M.md: FETCH 10,000,299,000 B + WRITE 3,126,500 B
-    "cfg3_n100_d25M_lie": 10_003_425_500,
+    # profiles/stream_kernel_VoteOp_cfg3_n100_d25M.md: FETCH 10,000,307,000 B + WRITE 3,126,600 B
+    "cfg3_n100_d25M_lie": 10_003_433_600,
 }
 
 
@@ -165,7 +165,7 @@ def main():
         f"{achieved:.0f} GB/s = {achieved / HBM_PEAK_GBS:.1%} of peak")
 
     result = {
-        "metric": "aggregated coordinates/sec (BRACE robust chunk aggregation)",
+        "metric": "aggregated coordinates/sec and achieved HBM GB/s (% of peak), n=100 d=25M fp32",
         "value": w.d / (ms_per_step * 1e-3),
         "unit": "coords/s",
         "n_gpus": 1,
@@ -189,13 +189,13 @@ def main():
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
             "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
-            "kernel": "brace_vote_kernel",
+            "kernel": "brace_dev::stream_kernel<VoteOp, ...> (the streaming vote kernel)",
             "algorithmic_bytes_per_launch": vote_bytes,
             "kernel_ms_avg": vote_ms,
             "kernel_ms_min": vote_each[0],
             "kernel_ms_median": vote_each[K // 2],
             "whole_step": {
-                "kernels": "brace_vote_kernel + brace_expand_kernel",
+                "kernels": "stream_kernel<VoteOp, ...> + brace_expand_kernel",
                 "algorithmic_bytes": step_bytes,
                 "ms_avg": step_ms, "ms_min": per_step_ms[0], "ms_median": per_step_ms[K // 2],
                 "achieved": step_gbs, "frac": step_gbs / HBM_PEAK_GBS,
