@@ -91,6 +91,9 @@ def main():
                          "linear-access bandwidth, reported under 'probe')")
     ap.add_argument("--probe", dest="probe", action="store_true", help=argparse.SUPPRESS)
     ap.set_defaults(probe=True)
+    ap.add_argument("--no-next-rows", dest="next_rows", action="store_false",
+                    help="skip timing the other entry points (sum/mean, fused update, bit planes)")
+    ap.set_defaults(next_rows=True)
     ap.add_argument("--tuning", default="",
                     help="vec,cols,unroll,nontemporal,xcd_swizzle (default: library defaults)")
     args = ap.parse_args()
@@ -202,6 +205,48 @@ def main():
             },
         },
     }
+    if args.next_rows:
+        # The widened rows, each timed alone with events on the launch stream and priced with
+        # its own algorithmic bytes (read the matrix once + what it must write / re-read).
+        rw = B.brace_packed_row_words(w.d)
+        signs = torch.empty(w.n, rw, device=dev, dtype=torch.int32)
+        model = torch.zeros(w.d, device=dev, dtype=torch.float32)
+        nd4 = 4 * w.n * w.d
+        rows = (
+            ("rar_mean", lambda: B.brace_rar_aggregate(upd, out, mean=True, stream=stream),
+             nd4 + 4 * w.d),
+            ("update_with_bits", lambda: B.brace_aggregate_update(upd, w.f, model, 1e-3, args.lam,
+                                                                  out_bits=bits, stream=stream),
+             nd4 + 8 * w.d + 2 * 4 * ((w.d + 31) // 32)),
+            ("update_direct", lambda: B.brace_aggregate_update(upd, w.f, model, 1e-3, args.lam,
+                                                               stream=stream), nd4 + 8 * w.d),
+            ("quantize", lambda: B.brace_quantize(upd, signs, stream=stream), nd4 + 4 * w.n * rw),
+            ("vote_packed", lambda: B.brace_vote_packed(signs, w.d, w.f, args.lam, out=out,
+                                                        stream=stream),
+             4 * w.n * rw + 4 * w.d + 2 * 4 * ((w.d + 31) // 32)),
+            ("expand_bits", lambda: B.brace_expand_bits(bits, w.d, out, stream=stream),
+             4 * w.d + 4 * ((w.d + 31) // 32)),
+            ("apply_bits", lambda: B.brace_apply_bits(bits, w.d, 1e-3, model, stream=stream),
+             8 * w.d + 4 * ((w.d + 31) // 32)),
+        )
+        extra = {}
+        for name, fn, nbytes in rows:
+            for _ in range(2):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = max(5, K // 3)
+            e0.record(stream)
+            for _ in range(reps):
+                fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            gbs = nbytes / (ms * 1e-3) / 1e9
+            extra[name] = {"ms": ms, "algorithmic_bytes": nbytes, "achieved_GBps": gbs,
+                           "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
+            log(f"[bench] {name}: {ms:.3f} ms, {gbs:.0f} GB/s ({gbs / HBM_PEAK_GBS:.1%})")
+        result["next_rows"] = extra
+        del signs, model
     if args.probe:
         nel = (1 << 30) // 4
         src = torch.randn(nel, device=dev)
