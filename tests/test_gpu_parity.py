@@ -109,6 +109,20 @@ def test_small_shapes_bit_exact(n, d, ld, offset):
             check_against_oracle(upd, 0, lam, zs)
 
 
+@pytest.mark.parametrize("n,d", [(1000, 700), (4097, 300), (32767, 130)])
+def test_many_clients(n, d):
+    # n up to the ABI limit (sign-sums are int16): counters, row split and int16 sums hold.
+    upd = special_matrix(n, d, seed=n)
+    f = n // 5
+    for lam in (0.0, 5.0, float(f), float(n - 1), -float(n)):
+        check_against_oracle(upd, f, lam)
+    ones = torch.ones(n, d, device=DEV)
+    out, bits, sums = gpu_aggregate(ones, 0, n - 1.0)
+    assert (sums == n).all() and (out == 1.0).all()          # S = n exactly, > n - 1
+    out, bits, sums = gpu_aggregate(-ones, 0, -float(n) - 0.5)
+    assert (sums == -n).all() and (out == 1.0).all()         # S = -n > -n - 0.5
+
+
 def test_lambda_sweep_bit_exact():
     n, f, d = 25, 5, 9001
     upd = special_matrix(n, d, seed=77)
