@@ -44,6 +44,21 @@ def test_library_exports_every_declared_symbol(L):
     assert set(B.EXPORTS) <= set(declared)
 
 
+def test_header_is_plain_c_and_host_entry_points_work_from_c(L, tmp_path):
+    # gcc -std=c99 -pedantic on the header, a C program linked against the library, no GPU call.
+    import subprocess
+    exe = str(tmp_path / "abi_host")
+    src = os.path.join(ROOT, "tests", "c", "abi_host.c")
+    libdir = os.path.dirname(B.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic",
+                    "-I", os.path.join(ROOT, "include"), src, "-o", exe,
+                    "-L", libdir, "-lbrace", "-lm", f"-Wl,-rpath,{libdir}",
+                    "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    res = subprocess.run([exe], capture_output=True, text=True)
+    assert res.returncode == 0, res.stdout + res.stderr
+    assert "abi_host ok" in res.stdout
+
+
 def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(B.BraceParams) == 40
     assert B.BraceParams.ld.offset == 16

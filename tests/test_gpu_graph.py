@@ -1,0 +1,75 @@
+"""The entry points allocate nothing and record no memset, so they can be captured in a HIP
+graph.  Each graph is replayed several times, with eager work and synchronisations between
+the replays and with the input changed in place, and every replay is checked against the CPU
+oracle (not only against the eager run)."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import brace_oracle as O
+from paper_2501_17392_amd import binding as B
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def fill(upd, seed):
+    g = torch.Generator(DEV).manual_seed(seed)
+    upd.copy_(torch.randn(upd.shape, device=DEV, generator=g))
+    upd[:, ::7] = 0.0
+
+
+def test_chunk_loop_and_whole_call_in_a_graph():
+    assert torch.cuda.is_available()
+    B.lib()
+    B.brace_reset_tuning()
+    n, d, f, lam = 20, 300_007, 4, 2.0
+    upd = torch.empty(n, d, device=DEV)
+    fill(upd, 0)
+    out_chunks = torch.zeros(d, device=DEV)
+    out_whole = torch.zeros(d, device=DEV)
+    bits = torch.zeros((d + 31) // 32, device=DEV, dtype=torch.int32)
+    mean = torch.zeros(d, device=DEV)
+    model = torch.zeros(d, device=DEV)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        # warm-up outside the capture (first launches load the code objects)
+        B.brace_aggregate(upd, f, lam, out=out_whole, out_bits=bits)
+        B.brace_rar_aggregate(upd, mean, mean=True)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            for c in range(n):
+                B.brace_aggregate_chunk(upd, f, c, lam, out=out_chunks)
+            B.brace_aggregate(upd, f, lam, out=out_whole, out_bits=bits)
+            B.brace_rar_aggregate(upd, mean, mean=True)
+            B.brace_apply_bits(bits, d, 0.5, model)
+    torch.cuda.synchronize()
+
+    applied = np.zeros(d, dtype=np.float64)
+    for replay in range(4):
+        fill(upd, 100 + replay)                       # eager work between replays
+        out_chunks.fill_(7.0)
+        out_whole.fill_(7.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        host = upd.cpu().numpy()
+        want = O.brace_direct(host, lam)
+        assert np.array_equal(out_chunks.cpu().numpy(), want.out), replay
+        assert np.array_equal(out_whole.cpu().numpy(), want.out), replay
+        assert np.array_equal(bits.cpu().numpy().view(np.uint8)[: (d + 7) // 8], want.bits), replay
+        got_mean = mean.cpu().numpy().astype(np.float64)
+        ref_mean = O.mean_direct(host)
+        assert np.all(np.abs(got_mean - ref_mean) <= 1e-6 + 1e-5 * np.abs(ref_mean)), replay
+        applied = O.model_update(applied.astype(np.float32), want.out, 0.5)
+        assert np.allclose(model.cpu().numpy(), applied, rtol=1e-5, atol=1e-6), replay
+        # an eager call in between gives the same thing
+        eager = torch.zeros(d, device=DEV)
+        B.brace_aggregate(upd, f, lam, out=eager)
+        torch.cuda.synchronize()
+        assert torch.equal(eager, out_whole)
