@@ -299,12 +299,14 @@ struct Shape {
 
 // Explicit tuning values win; zeros mean "choose from the size of the range".  Large ranges
 // want long contiguous runs per wave (8 loads per row, 2 rows per batch, double-buffered:
-// 32 KiB in flight per wave at 4-dword loads).  Short ranges shrink the tile until there are
-// about 4 waves per SIMD, and below that split the client rows over the waves of a block.
+// 32 KiB in flight per wave at 4-dword loads).  Shorter ranges shrink the tile until there are
+// about 2 waves per SIMD (measured on single ring chunks of cfg 2-4: one load per row with 4
+// rows per batch beats wider tiles and beats splitting rows); only when there are fewer
+// waves than compute units do the waves of a block split the client rows.
 Shape choose_shape(const brace_tuning_t& t, int64_t slots, int64_t n)
 {
     const int64_t cus = compute_units() > 0 ? compute_units() : 256;
-    const int64_t target = 16 * cus;               // 4 SIMDs per CU x 4 waves
+    const int64_t target = 8 * cus;                // 4 SIMDs per CU x 2 waves
     Shape s;
     s.cols = t.cols;
     if (s.cols == 0) {
@@ -313,14 +315,14 @@ Shape choose_shape(const brace_tuning_t& t, int64_t slots, int64_t n)
             s.cols >>= 1;
     }
     if (t.rowsplit == 0)
-        s.rowsplit = (n >= 2 * kWaves && slots / s.cols < target / 2) ? 1 : 0;
+        s.rowsplit = (n >= 2 * kWaves && slots / s.cols < cus) ? 1 : 0;
     else
         s.rowsplit = t.rowsplit == 2 ? 1 : 0;
     if (s.rowsplit && s.cols > kRowsplitMaxCols)
         s.cols = kRowsplitMaxCols;
     s.unroll = t.unroll;
     if (s.unroll == 0) {
-        s.unroll = s.cols >= 8 ? 2 : (s.cols >= 4 ? 4 : 8);
+        s.unroll = s.cols >= 8 ? 2 : 4;
         const int64_t rows = s.rowsplit ? n / kWaves : n;
         while (s.unroll > 2 && 2 * s.unroll > rows)
             s.unroll >>= 1;
