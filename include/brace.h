@@ -179,6 +179,15 @@ int brace_rar_aggregate(const float* updates_dev, int64_t n, int64_t d,
 int brace_rar_aggregate_chunk(const float* updates_dev, int64_t n, int64_t d, int64_t chunk,
                               const brace_rar_params_t* params, float* out_dev, void* hip_stream);
 
+/*
+ * Before a call enqueues anything, every buffer is checked on the host: it must be device
+ * memory known to the HIP runtime, and the bytes the call will touch (from the sizes given)
+ * must lie inside the allocation that holds the pointer; otherwise the call returns
+ * BRACE_EINVAL and launches nothing.  On by default (two runtime queries per buffer, about a
+ * microsecond each); process-wide switch for callers that cannot afford them.
+ */
+int brace_set_pointer_checks(int32_t enabled);
+
 /* Text of the last error on the calling thread ("" if none).  Static storage; do not free. */
 const char* brace_last_error(void);
 

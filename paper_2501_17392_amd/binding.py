@@ -68,6 +68,7 @@ EXPORTS = (
     "brace_probe_read", "brace_probe_copy", "brace_rar_aggregate", "brace_rar_aggregate_chunk",
     "brace_aggregate_update", "brace_aggregate_update_chunk", "brace_expand_bits", "brace_apply_bits",
     "brace_packed_row_words", "brace_quantize", "brace_vote_packed", "brace_aggregate_chunks",
+    "brace_set_pointer_checks",
 )
 
 
@@ -125,6 +126,8 @@ def lib():
     L.brace_quantize.restype = ctypes.c_int
     L.brace_vote_packed.argtypes = [vp, i64, i64, i64, i64, pp, vp, vp]
     L.brace_vote_packed.restype = ctypes.c_int
+    L.brace_set_pointer_checks.argtypes = [ctypes.c_int32]
+    L.brace_set_pointer_checks.restype = ctypes.c_int
     rp = ctypes.POINTER(BraceRarParams)
     L.brace_rar_aggregate.argtypes = [vp, i64, i64, rp, vp, vp]
     L.brace_rar_aggregate.restype = ctypes.c_int
@@ -318,3 +321,8 @@ def brace_aggregate_chunks(updates, f: int, chunk_begin: int, chunk_end: int, la
     _check(lib().brace_aggregate_chunks(updates.data_ptr(), n, d, f, chunk_begin, chunk_end,
                                         ctypes.byref(p), _ptr(out), _stream_handle(stream)))
     return out
+
+
+def brace_set_pointer_checks(enabled: bool):
+    """Host-side validation of every device buffer before a launch (on by default)."""
+    _check(lib().brace_set_pointer_checks(1 if enabled else 0))

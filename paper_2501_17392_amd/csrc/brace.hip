@@ -367,6 +367,58 @@ int64_t plan_range(StreamArgs& a, Shape& shape, const brace_tuning_t& t, int64_t
     return body_blocks + a.edge_blocks;
 }
 
+// Before anything is enqueued: every buffer must be device memory and the bytes the kernels
+// will touch must lie inside the allocation that holds the pointer.  A wrong shape is then
+// an error code on the host instead of a memory fault on the device.  Can be switched off
+// (brace_set_pointer_checks) by callers that cannot afford the two runtime queries per buffer.
+bool g_pointer_checks = true;
+
+int check_device_range(const void* ptr, int64_t bytes, const char* name)
+{
+    if (!g_pointer_checks || !ptr || bytes <= 0)
+        return BRACE_OK;
+    hipPointerAttribute_t attr;
+    hipError_t err = hipPointerGetAttributes(&attr, ptr);
+    if (err != hipSuccess) {
+        (void)hipGetLastError();                   // do not leave the error for the next launch check
+        return fail(BRACE_EINVAL, "%s is not a device pointer known to the HIP runtime (%s)", name,
+                    hipGetErrorString(err));
+    }
+    if (attr.type != hipMemoryTypeDevice && attr.type != hipMemoryTypeManaged &&
+        attr.type != hipMemoryTypeUnified)
+        return fail(BRACE_EINVAL, "%s is not device memory", name);
+    hipDeviceptr_t base = nullptr;
+    size_t size = 0;
+    err = hipMemGetAddressRange(&base, &size, const_cast<void*>(ptr));
+    if (err != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(BRACE_EINVAL, "%s: cannot query its allocation (%s)", name, hipGetErrorString(err));
+    }
+    const uintptr_t p = reinterpret_cast<uintptr_t>(ptr);
+    const uintptr_t b = reinterpret_cast<uintptr_t>(base);
+    if (p < b || (uint64_t)bytes > (uint64_t)size || p - b > size - (uint64_t)bytes)
+        return fail(BRACE_EINVAL, "%s: the call needs %lld bytes from this pointer but its allocation "
+                                  "ends after %lld", name, (long long)bytes,
+                    (long long)(size - (size_t)(p - b)));
+    return BRACE_OK;
+}
+
+// The buffers of a vote / sum / update call over the FULL vectors (chunk calls address them too).
+int check_buffers(const float* updates, int64_t n, int64_t d, int64_t ld, const float* out,
+                  const void* bits, const void* sums, const float* w)
+{
+    int rc = check_device_range(updates, ((n - 1) * ld + d) * 4, "updates_dev");
+    if (rc == BRACE_OK)
+        rc = check_device_range(out, d * 4, "out_dev");
+    if (rc == BRACE_OK)
+        rc = check_device_range(bits, ((d + 31) / 32) * 4, "out_bits_dev");
+    if (rc == BRACE_OK)
+        rc = check_device_range(sums, d * 2, "sums_dev");
+    if (rc == BRACE_OK)
+        rc = check_device_range(w, d * 4, "w_dev");
+    return rc;
+}
+
 int check_launch(const char* what)
 {
     const hipError_t err = hipGetLastError();
@@ -381,6 +433,9 @@ int launch_vote(const float* updates, int64_t n, int64_t d, int64_t ld, int thre
 {
     if (hi <= lo)
         return BRACE_OK;
+    int rc = check_buffers(updates, n, d, ld, out, p->out_bits_dev, p->sums_dev, w);
+    if (rc != BRACE_OK)
+        return rc;
     const brace_tuning_t t = g_tuning;
     int v = pick_width(updates, n, ld, out, p->sums_dev, t.vec);
     if (w)
@@ -436,7 +491,7 @@ int launch_vote(const float* updates, int64_t n, int64_t d, int64_t ld, int thre
     }
     const size_t lds = sh.rowsplit ? sizeof(VoteOp::State) * (kWaves - 1) * sh.cols * v * 64 : 0;
     hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(kBlock), lds, stream, updates, a, op);
-    int rc = check_launch("vote kernel");
+    rc = check_launch("vote kernel");
     if (rc != BRACE_OK)
         return rc;
     if (split) {
@@ -457,11 +512,14 @@ int launch_vote(const float* updates, int64_t n, int64_t d, int64_t ld, int thre
     return rc;
 }
 
-int launch_sum(const float* updates, int64_t n, int64_t ld, double scale, float* out, int64_t lo,
-               int64_t hi, hipStream_t stream)
+int launch_sum(const float* updates, int64_t n, int64_t d, int64_t ld, double scale, float* out,
+               int64_t lo, int64_t hi, hipStream_t stream)
 {
     if (hi <= lo)
         return BRACE_OK;
+    const int rc = check_buffers(updates, n, d, ld, out, nullptr, nullptr, nullptr);
+    if (rc != BRACE_OK)
+        return rc;
     const brace_tuning_t t = g_tuning;
     const int v = pick_width(updates, n, ld, out, nullptr, t.vec);
     SumOp op;
@@ -671,9 +729,15 @@ static int launch_from_bits(const uint32_t* bits, int64_t d, float* out, float* 
 {
     if (d == 0)
         return BRACE_OK;
+    int rc = check_device_range(bits, ((d + 31) / 32) * 4, "bits_dev");
+    if (rc == BRACE_OK)
+        rc = check_device_range(out, d * 4, "out_dev");
+    if (rc == BRACE_OK)
+        rc = check_device_range(w, d * 4, "w_dev");
+    if (rc != BRACE_OK)
+        return rc;
     float* target = out ? out : w;
     const int64_t groups = aligned_to(target, 16) ? d / kGroup : 0;
-    int rc = BRACE_OK;
     if (groups > 0) {
         const int64_t egrid = (groups + kWaves - 1) / kWaves;
         if (egrid > 0x7fffffffLL)
@@ -751,6 +815,12 @@ int brace_quantize(const float* updates_dev, int64_t n, int64_t d, int64_t ld,
     if (!updates_dev || !signs_dev || !aligned_to(updates_dev, 4) || !aligned_to(signs_dev, 16))
         return fail(BRACE_EINVAL, "updates_dev (4-byte aligned) and signs_dev (16-byte aligned) "
                                   "must be non-NULL");
+    int rc = check_device_range(updates_dev, ((n - 1) * ld + d) * 4, "updates_dev");
+    if (rc == BRACE_OK)
+        rc = check_device_range(signs_dev, ((n - 1) * ld_words + brace_packed_row_words(d)) * 4,
+                                "signs_dev");
+    if (rc != BRACE_OK)
+        return rc;
     const int64_t spans = (d + kQuantSpan - 1) / kQuantSpan;
     const int64_t tasks = spans * n;
     const int64_t grid = (tasks + kWaves - 1) / kWaves;
@@ -822,6 +892,14 @@ int brace_vote_packed(const uint32_t* signs_dev, int64_t n, int64_t d, int64_t l
         c = (ni + thresh + 1) / 2;
     }
 
+    int rc = check_device_range(signs_dev, ((n - 1) * ld_words + brace_packed_row_words(d)) * 4,
+                                "signs_dev");
+    if (rc == BRACE_OK)
+        rc = check_device_range(out_dev, d * 4, "out_dev");
+    if (rc == BRACE_OK)
+        rc = check_device_range(bits, ((d + 31) / 32) * 4, "out_bits_dev");
+    if (rc != BRACE_OK)
+        return rc;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int64_t cols4 = brace_packed_row_words(d) / 4;
     const int64_t grid = (cols4 + kBlock - 1) / kBlock;
@@ -837,7 +915,7 @@ int brace_vote_packed(const uint32_t* signs_dev, int64_t n, int64_t d, int64_t l
     else
         hipLaunchKernelGGL(brace_vote_packed_kernel<16>, dim3((unsigned)grid), dim3(kBlock), 0, stream,
                            planes, ld_words / 4, ni, cols4, mask_p, mask_n, c, dst, scratch, d);
-    int rc = check_launch("packed vote kernel");
+    rc = check_launch("packed vote kernel");
     if (rc != BRACE_OK || !out_dev)
         return rc;
     const int64_t groups = (d + kGroup - 1) / kGroup;
@@ -855,7 +933,7 @@ int brace_rar_aggregate(const float* updates_dev, int64_t n, int64_t d,
     const int rc = validate_rar(updates_dev, n, d, params, out_dev, &ld, &scale);
     if (rc != BRACE_OK)
         return rc;
-    return launch_sum(updates_dev, n, ld, scale, out_dev, 0, d,
+    return launch_sum(updates_dev, n, d, ld, scale, out_dev, 0, d,
                       static_cast<hipStream_t>(hip_stream));
 }
 
@@ -871,7 +949,7 @@ int brace_rar_aggregate_chunk(const float* updates_dev, int64_t n, int64_t d, in
     rc = brace_chunk_range(n, d, chunk, &lo, &hi);
     if (rc != BRACE_OK)
         return rc;
-    return launch_sum(updates_dev, n, ld, scale, out_dev, lo, hi,
+    return launch_sum(updates_dev, n, d, ld, scale, out_dev, lo, hi,
                       static_cast<hipStream_t>(hip_stream));
 }
 
@@ -906,6 +984,12 @@ int brace_get_tuning(brace_tuning_t* tuning)
     if (!tuning)
         return fail(BRACE_EINVAL, "tuning is NULL");
     *tuning = g_tuning;
+    return BRACE_OK;
+}
+
+int brace_set_pointer_checks(int32_t enabled)
+{
+    g_pointer_checks = enabled != 0;
     return BRACE_OK;
 }
 

@@ -414,3 +414,48 @@ def test_cfg3_full_headline():
 def test_cfg4_full_sparse_mix():
     w = synth.WORKLOADS[4]
     assert _full_size_check(w, (5.0,), col_tile=4_000_000) > 0
+
+
+# --------------------------------------------------------------------------
+# Host-side buffer checks: a wrong shape is an error code, not a GPU fault
+# --------------------------------------------------------------------------
+
+def test_wrong_buffers_are_rejected_on_the_host():
+    small = torch.zeros(1000, device=DEV)
+    out = torch.zeros(1000, device=DEV)
+    import ctypes
+    # one client, but a dimension far beyond what the buffers hold
+    with pytest.raises(B.BraceError) as ei:
+        bits = torch.zeros(200_000_000 // 32, device=DEV, dtype=torch.int32)
+        p = B.make_params(5.0, 0, 0, bits.data_ptr(), None)
+        B._check(B.lib().brace_aggregate(small.data_ptr(), 1, 200_000_000, 0, ctypes.byref(p),
+                                         None, None))
+    assert ei.value.code == B.BRACE_EINVAL and "allocation" in ei.value.text
+    big = torch.zeros(4, 100_000, device=DEV)
+    with pytest.raises(B.BraceError) as ei:                    # out too short for d
+        p = B.make_params(5.0, 0, 100_000, None, None)
+        rc = B.lib().brace_aggregate(big.data_ptr(), 4, 100_000_000, 0, ctypes.byref(p),
+                                     out.data_ptr(), None)
+        B._check(rc)
+    assert ei.value.code == B.BRACE_EINVAL
+    pinned = torch.zeros(1000, pin_memory=True)
+    with pytest.raises(B.BraceError) as ei:                    # host memory is not accepted
+        p = B.make_params(5.0, 0, 0, None, None)
+        B._check(B.lib().brace_aggregate(big.data_ptr(), 4, 1000, 0, ctypes.byref(p),
+                                         pinned.data_ptr(), None))
+    assert ei.value.code == B.BRACE_EINVAL
+    with pytest.raises(B.BraceError):
+        B.brace_expand_bits(torch.zeros(4, device=DEV, dtype=torch.int32), 200_000_000, out)
+    # nothing above launched anything or left an error behind: a good call still works
+    good = torch.empty(100_000, device=DEV)
+    B.brace_aggregate(big, 0, 0.0, out=good)
+    torch.cuda.synchronize()
+    assert (good == -1.0).all()
+    # switched off, the same good call works too
+    B.brace_set_pointer_checks(False)
+    try:
+        B.brace_aggregate(big, 0, -1.0, out=good)
+        torch.cuda.synchronize()
+        assert (good == 1.0).all()
+    finally:
+        B.brace_set_pointer_checks(True)
