@@ -95,7 +95,8 @@ def main():
                     help="skip timing the other entry points (sum/mean, fused update, bit planes)")
     ap.set_defaults(next_rows=True)
     ap.add_argument("--tuning", default="",
-                    help="vec,cols,unroll,nontemporal,xcd_swizzle (default: library defaults)")
+                    help="vec,cols,unroll,nontemporal,pipeline,split_writes,rowsplit (default: library "
+                         "defaults)")
     args = ap.parse_args()
 
     if args.gpus != 1:

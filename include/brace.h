@@ -201,9 +201,6 @@ typedef struct brace_tuning {
     int32_t  cols;         /* loads per lane per row: 1, 2, 4 or 8; 0 = from the size of the range */
     int32_t  unroll;       /* rows per batch of loads: 2, 4 or 8; 0 = from the size of the range  */
     int32_t  nontemporal;  /* 1: streaming (non-temporal) loads                                   */
-    int32_t  xcd_swizzle;  /* 1: give each of the 8 XCDs a contiguous span of the coordinates     */
-    int32_t  persist;      /* 0: one tile per block; k > 0: at most k blocks per compute unit,    */
-                           /* each walking several tiles (all resident waves share one panel)     */
     int32_t  pipeline;     /* 1: request the next batch of rows before consuming the current one  */
     int32_t  split_writes; /* fp32 output written by a second, write-only kernel from the bits:   */
                            /* 0 = for large ranges (default), 1 = never, 2 = whenever possible    */

@@ -37,8 +37,6 @@ class BraceTuning(ctypes.Structure):
         ("cols", ctypes.c_int32),
         ("unroll", ctypes.c_int32),
         ("nontemporal", ctypes.c_int32),
-        ("xcd_swizzle", ctypes.c_int32),
-        ("persist", ctypes.c_int32),
         ("pipeline", ctypes.c_int32),
         ("split_writes", ctypes.c_int32),
         ("rowsplit", ctypes.c_int32),
@@ -218,10 +216,9 @@ def brace_aggregate_chunk(updates, f: int, chunk: int, lam: float = 5.0, zero_si
 
 
 def brace_set_tuning(vec: int = 0, cols: int = 0, unroll: int = 0, nontemporal: int = 1,
-                     xcd_swizzle: int = 0, persist: int = 0, pipeline: int = 1,
-                     split_writes: int = 0, rowsplit: int = 0):
-    t = BraceTuning(ctypes.sizeof(BraceTuning), vec, cols, unroll, nontemporal, xcd_swizzle,
-                    persist, pipeline, split_writes, rowsplit)
+                     pipeline: int = 1, split_writes: int = 0, rowsplit: int = 0):
+    t = BraceTuning(ctypes.sizeof(BraceTuning), vec, cols, unroll, nontemporal, pipeline,
+                    split_writes, rowsplit)
     _check(lib().brace_set_tuning(ctypes.byref(t)))
 
 

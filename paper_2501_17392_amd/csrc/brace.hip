@@ -42,8 +42,6 @@ brace_tuning_t default_tuning()
     t.cols = 0;
     t.unroll = 0;
     t.nontemporal = 1;
-    t.xcd_swizzle = 0;
-    t.persist = 0;
     t.pipeline = 1;
     t.split_writes = 0;
     t.rowsplit = 0;
@@ -337,7 +335,7 @@ int64_t plan_range(StreamArgs& a, Shape& shape, const brace_tuning_t& t, int64_t
 {
     a.ld = ld;
     a.n = (int32_t)n;
-    a.swizzle = t.xcd_swizzle ? 1 : 0;
+    a.reserved = 0;
     a.lo = lo;
     a.hi = hi;
     a.hi_ext = hi_ext;
@@ -351,17 +349,7 @@ int64_t plan_range(StreamArgs& a, Shape& shape, const brace_tuning_t& t, int64_t
     const int64_t slots = (hi_a - lo_a) / (64 * (int64_t)v);
     shape = choose_shape(t, slots, n);
     const int64_t per_block = (shape.rowsplit ? 1 : (int64_t)kWaves) * shape.cols;
-    int64_t tiles = (slots + per_block - 1) / per_block;
-    if (a.swizzle)                 // the swizzled map needs a multiple of 8 tile ids
-        tiles = (tiles + kXcds - 1) / kXcds * kXcds;
-    int64_t body_blocks = tiles;
-    if (t.persist > 0) {
-        const int64_t resident = (int64_t)t.persist * compute_units();
-        if (resident > 0 && body_blocks > resident)
-            body_blocks = resident;
-    }
-    a.tiles = tiles;
-    a.body_blocks = body_blocks;
+    const int64_t body_blocks = (slots + per_block - 1) / per_block;
     const int64_t edge = (lo_a - lo) + (hi_ext - hi_a);
     a.edge_blocks = (edge + kBlock - 1) / kBlock;
     return body_blocks + a.edge_blocks;
@@ -970,11 +958,10 @@ int brace_set_tuning(const brace_tuning_t* tuning)
     const int v = tuning->vec, c = tuning->cols, u = tuning->unroll;
     if (!(v == 0 || v == 1 || v == 2 || v == 4) ||
         !(c == 0 || c == 1 || c == 2 || c == 4 || c == 8) ||
-        !(u == 0 || u == 2 || u == 4 || u == 8) || tuning->persist < 0 || tuning->persist > 64 ||
-        tuning->split_writes < 0 || tuning->split_writes > 2 || tuning->rowsplit < 0 ||
+        !(u == 0 || u == 2 || u == 4 || u == 8) || tuning->split_writes < 0 || tuning->split_writes > 2 || tuning->rowsplit < 0 ||
         tuning->rowsplit > 2)
-        return fail(BRACE_EINVAL, "tuning: vec in {0,1,2,4}, cols in {0,1,2,4,8}, unroll in {0,2,4,8}, persist in "
-                    "[0,64], split_writes and rowsplit in {0,1,2}");
+        return fail(BRACE_EINVAL, "tuning: vec in {0,1,2,4}, cols in {0,1,2,4,8}, unroll in {0,2,4,8}, "
+                    "split_writes and rowsplit in {0,1,2}");
     g_tuning = *tuning;
     return BRACE_OK;
 }

@@ -46,7 +46,6 @@ namespace brace_dev {
 #endif
 constexpr int kBlock = BRACE_BLOCK;         // threads per block (waves of 64)
 constexpr int kWaves = kBlock / 64;
-constexpr int kXcds = 8;                    // MI355X: 8 XCDs, blocks are dealt round-robin
 
 template <int V> struct Vec;
 template <> struct Vec<1> { typedef float type; };
@@ -97,13 +96,11 @@ __device__ __forceinline__ void store_vec(T* p, const T& v)
 struct StreamArgs {
     int64_t ld;             // row i at updates + i*ld
     int32_t n;
-    int32_t swizzle;        // XCD-aware block -> tile map
+    int32_t reserved;
     int64_t lo, hi;         // coordinates of this call
     int64_t lo_a, hi_a;     // aligned body
     int64_t hi_ext;         // edges run up to here; [hi, hi_ext) is op-specific padding
     int64_t edge_blocks;    // blocks [0, edge_blocks) run the edges, the rest the body
-    int64_t body_blocks;    // blocks that run the body
-    int64_t tiles;          // tiles in the body; body block b takes tiles b, b + body_blocks, ...
 };
 
 // One wave folds rows [0, n) starting at `updates` (already offset to its first row) for
@@ -220,7 +217,7 @@ __device__ __forceinline__ void stream_slots(const float* __restrict__ updates, 
                     for (int e = 0; e < V; ++e)
                         Op::merge(st[c][e], lds[(w * (COLS * V) + c * V + e) * 64 + lane]);
         }
-        __syncthreads();                        // LDS is reused by the block's next tile
+        __syncthreads();                        // LDS is reused by the next slot of a ragged tile
         if (wave > 0)
             return;
     }
@@ -276,29 +273,20 @@ stream_kernel(const float* __restrict__ updates, const StreamArgs a, const Op op
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     constexpr int64_t kSlot = 64 * V;
     const int64_t slots = (a.hi_a - a.lo_a) / kSlot;
-    // With body_blocks == tiles every block runs one tile.  With fewer (resident) blocks a
-    // block walks tiles b, b + body_blocks, ...
-    for (int64_t t = b; t < a.tiles; t += a.body_blocks) {
-        // Blocks are dealt to the 8 XCDs round-robin.  With the swizzle, XCD x works on the
-        // x-th eighth of the tiles, so neighbouring tiles (which share boundary cache lines
-        // when rows are not line-aligned) meet in the same L2.
-        int64_t tile = t;
-        if (a.swizzle) {
-            const int64_t per = a.tiles / kXcds;       // tiles is a multiple of 8 here
-            tile = (t % kXcds) * per + t / kXcds;
-        }
-        // Row split: all waves of the block share the tile's COLS slots (block-uniform flow).
-        const int64_t s0 = RS ? tile * COLS : (tile * kWaves + wave) * COLS;
-        if (s0 >= slots)
-            continue;
-        if (s0 + COLS <= slots) {
-            stream_slots<Op, V, COLS, RU, NT, PIPE, RS>(updates, a.ld, a.n, a.lo_a + s0 * kSlot,
-                                                        lane, wave, op);
-        } else {
-            for (int64_t s = s0; s < slots; ++s)   // fewer than COLS slots left at the very end
-                stream_slots<Op, V, 1, RU, NT, PIPE, RS>(updates, a.ld, a.n, a.lo_a + s * kSlot,
-                                                         lane, wave, op);
-        }
+    // One tile per block.  (Measured and dropped: an XCD-aware block -> tile map and resident
+    // blocks walking several tiles; neither moved the time by more than noise.)
+    const int64_t tile = b;
+    // Row split: all waves of the block share the tile's COLS slots (block-uniform flow).
+    const int64_t s0 = RS ? tile * COLS : (tile * kWaves + wave) * COLS;
+    if (s0 >= slots)
+        return;
+    if (s0 + COLS <= slots) {
+        stream_slots<Op, V, COLS, RU, NT, PIPE, RS>(updates, a.ld, a.n, a.lo_a + s0 * kSlot, lane,
+                                                    wave, op);
+    } else {
+        for (int64_t s = s0; s < slots; ++s)       // fewer than COLS slots left at the very end
+            stream_slots<Op, V, 1, RU, NT, PIPE, RS>(updates, a.ld, a.n, a.lo_a + s * kSlot, lane,
+                                                     wave, op);
     }
 }
 

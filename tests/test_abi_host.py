@@ -64,7 +64,7 @@ def test_struct_layouts_match_the_header():
     assert B.BraceParams.ld.offset == 16
     assert B.BraceParams.out_bits_dev.offset == 24
     assert B.BraceParams.sums_dev.offset == 32
-    assert ctypes.sizeof(B.BraceTuning) == 40
+    assert ctypes.sizeof(B.BraceTuning) == 32
 
 
 def test_params_init_defaults(L):
@@ -239,19 +239,16 @@ def test_rar_aggregate_rejects_invalid_arguments(L):
 def test_tuning_roundtrip_and_validation(L):
     B.brace_reset_tuning()
     base = B.brace_get_tuning()
-    assert set(base) == {"vec", "cols", "unroll", "nontemporal", "xcd_swizzle", "persist",
-                         "pipeline", "split_writes", "rowsplit"}
-    B.brace_set_tuning(vec=2, cols=4, unroll=8, nontemporal=0, xcd_swizzle=1, persist=3,
-                       pipeline=0, split_writes=2, rowsplit=2)
+    assert set(base) == {"vec", "cols", "unroll", "nontemporal", "pipeline", "split_writes",
+                         "rowsplit"}
+    B.brace_set_tuning(vec=2, cols=4, unroll=8, nontemporal=0, pipeline=0, split_writes=2,
+                       rowsplit=2)
     assert B.brace_get_tuning() == {"vec": 2, "cols": 4, "unroll": 8, "nontemporal": 0,
-                                    "xcd_swizzle": 1, "persist": 3, "pipeline": 0,
-                                    "split_writes": 2, "rowsplit": 2}
+                                    "pipeline": 0, "split_writes": 2, "rowsplit": 2}
     with pytest.raises(B.BraceError):
         B.brace_set_tuning(rowsplit=3)
     with pytest.raises(B.BraceError):
         B.brace_set_tuning(split_writes=3)
-    with pytest.raises(B.BraceError):
-        B.brace_set_tuning(persist=-1)
     with pytest.raises(B.BraceError):
         B.brace_set_tuning(vec=3)
     with pytest.raises(B.BraceError):

@@ -311,12 +311,11 @@ def test_all_tunings_agree_with_the_oracle():
             for vec in (0, 1, 2, 4):
                 for cols in (1, 2, 4, 8):
                     for unroll in (2, 4, 8):
-                        for nt, sw, persist, pipe, split, rs in (
-                                (0, 0, 0, 0, 1, 1), (1, 0, 0, 0, 2, 2), (1, 1, 0, 1, 1, 2),
-                                (1, 0, 1, 0, 2, 1), (0, 1, 2, 1, 2, 2), (1, 0, 0, 1, 0, 0)):
-                            B.brace_set_tuning(vec, cols, unroll, nt, sw, persist, pipe, split, rs)
+                        for nt, pipe, split, rs in ((0, 0, 1, 1), (1, 0, 2, 2), (1, 1, 1, 2),
+                                                    (0, 1, 2, 1), (1, 1, 0, 0)):
+                            B.brace_set_tuning(vec, cols, unroll, nt, pipe, split, rs)
                             out, bits, sums = gpu_aggregate(view, 0, 2.0)
-                            tag = (ld, off, vec, cols, unroll, nt, sw, persist, pipe, split, rs)
+                            tag = (ld, off, vec, cols, unroll, nt, pipe, split, rs)
                             assert np.array_equal(out, want.out), tag
                             assert np.array_equal(sums.astype(np.int64), want.sums), tag
                             assert np.array_equal(bits[: (d + 7) // 8], want.bits), tag

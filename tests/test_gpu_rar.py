@@ -139,14 +139,13 @@ def test_tunings_agree():
         for vec in (0, 1, 2, 4):
             for cols in (1, 2, 4, 8):
                 for unroll in (2, 4, 8):
-                    for nt, sw, persist, pipe, rs in ((0, 0, 0, 0, 1), (1, 1, 0, 1, 1), (1, 0, 2, 1, 1),
-                                                      (1, 0, 0, 1, 2), (0, 1, 2, 0, 2)):
-                        B.brace_set_tuning(vec, cols, unroll, nt, sw, persist, pipe, 0, rs)
+                    for nt, pipe, rs in ((0, 0, 1), (1, 1, 1), (1, 1, 2), (0, 0, 2)):
+                        B.brace_set_tuning(vec, cols, unroll, nt, pipe, 0, rs)
                         out = torch.empty(d, device=DEV, dtype=torch.float32)
                         B.brace_rar_aggregate(upd, out)
                         torch.cuda.synchronize()
                         got = out.cpu().numpy()
-                        assert close(got, want), (vec, cols, unroll, nt, sw, persist, pipe, rs)
+                        assert close(got, want), (vec, cols, unroll, nt, pipe, rs)
                         if rs == 1:
                             if ref is None:
                                 ref = got
