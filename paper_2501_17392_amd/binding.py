@@ -40,6 +40,7 @@ class BraceTuning(ctypes.Structure):
         ("pipeline", ctypes.c_int32),
         ("split_writes", ctypes.c_int32),
         ("rowsplit", ctypes.c_int32),
+        ("stage_writes", ctypes.c_int32),
     ]
 
 
@@ -216,9 +217,10 @@ def brace_aggregate_chunk(updates, f: int, chunk: int, lam: float = 5.0, zero_si
 
 
 def brace_set_tuning(vec: int = 0, cols: int = 0, unroll: int = 0, nontemporal: int = 1,
-                     pipeline: int = 1, split_writes: int = 0, rowsplit: int = 0):
+                     pipeline: int = 1, split_writes: int = 0, rowsplit: int = 0,
+                     stage_writes: int = 0):
     t = BraceTuning(ctypes.sizeof(BraceTuning), vec, cols, unroll, nontemporal, pipeline,
-                    split_writes, rowsplit)
+                    split_writes, rowsplit, stage_writes)
     _check(lib().brace_set_tuning(ctypes.byref(t)))
 
 

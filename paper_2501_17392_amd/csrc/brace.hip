@@ -45,6 +45,7 @@ brace_tuning_t default_tuning()
     t.pipeline = 1;
     t.split_writes = 0;
     t.rowsplit = 0;
+    t.stage_writes = 0;
     return t;
 }
 
@@ -64,8 +65,6 @@ int compute_units()
 }
 
 brace_tuning_t g_tuning = default_tuning();
-
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // Second phase of a split call: one wave turns the 32 bit-words of a 1024-coordinate group
 // into 1024 floats.  `words` is the linear bit array, or null when the words were parked in
@@ -407,6 +406,65 @@ int check_buffers(const float* updates, int64_t n, int64_t d, int64_t ld, const 
     return rc;
 }
 
+// Staged (burst-write) launch: legal when the op writes one float per coordinate to 16-byte
+// aligned arrays with 2- or 4-dword accesses; chosen for ranges large enough to get the
+// widest tile anyway.  Returns the tiles per block (0 = use the ordinary kernel).
+int stage_tiles_for(const brace_tuning_t& t, const Shape& sh, int v, int64_t slots,
+                    const void* out, const void* w)
+{
+    if (t.stage_writes == 1 || (v != 2 && v != 4) || sh.rowsplit)
+        return 0;
+    if ((out && !aligned_to(out, 16)) || (w && !aligned_to(w, 16)))
+        return 0;
+    if (t.stage_writes != 2 && (t.cols != 0 || t.unroll != 0 || sh.cols != kStageCols))
+        return 0;                  // explicit tile tuning, or a short range: ordinary kernel
+    // The LDS burst limits a compute unit to one block, so the blocks run in rounds of one
+    // per unit and a last, part-filled round costs as much as a full one.  Among the burst
+    // sizes that fit, take the largest whose rounds are (nearly) as full as the best one.
+    const size_t tile_bytes = (size_t)kWaves * kStageCols * 64 * v * 4;
+    const int max_tiles = (int)(kStageBytes / tile_bytes);
+    const int64_t cus = compute_units() > 0 ? compute_units() : 256;
+    const int64_t tiles = (slots + kWaves * kStageCols - 1) / (kWaves * kStageCols);
+    int best = 0;
+    double best_fill = 0.0;
+    for (int k = 2; k <= max_tiles; ++k) {
+        const int64_t blocks = (tiles + k - 1) / k;
+        if (blocks < cus)
+            break;
+        const double fill = (double)blocks / (double)((blocks + cus - 1) / cus * cus);
+        if (fill >= 0.95 * best_fill) {
+            best = k;
+            if (fill > best_fill)
+                best_fill = fill;
+        }
+    }
+    if (t.stage_writes == 2 && best == 0 && slots > 0)
+        best = max_tiles;          // forced: correctness tests on inputs of any size
+    return best;
+}
+
+// Opt a kernel in to more than the default 64 KiB of dynamic LDS (once per kernel).
+int allow_stage_lds(const void* kernel)
+{
+    static const void* done[8] = {};
+    for (const void* k : done)
+        if (k == kernel)
+            return BRACE_OK;
+    const hipError_t err = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               (int)kStageBytes);
+    if (err != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(BRACE_EHIP, "cannot reserve %zu bytes of LDS: %s", kStageBytes,
+                    hipGetErrorString(err));
+    }
+    for (const void*& k : done)
+        if (!k) {
+            k = kernel;
+            break;
+        }
+    return BRACE_OK;
+}
+
 int check_launch(const char* what)
 {
     const hipError_t err = hipGetLastError();
@@ -468,6 +526,20 @@ int launch_vote(const float* updates, int64_t n, int64_t d, int64_t ld, int thre
         return fail(BRACE_ERANGE, "range needs %lld blocks, more than one launch can hold",
                     (long long)grid);
 
+    const int64_t slots = (a.hi_a - a.lo_a) / (64 * (int64_t)v);
+    const bool plain_floats = !split && !bits && !p->sums_dev && (out || w);
+    const int stage = plain_floats ? stage_tiles_for(t, sh, v, slots, out, w) : 0;
+    if (stage > 0) {
+        const int64_t per_block = (int64_t)stage * kWaves * kStageCols;
+        const int64_t sgrid = (slots + per_block - 1) / per_block + a.edge_blocks;
+        stream_staged_kernel_t<VoteOp> ks = brace_vote_pick_staged(v, t.pipeline);
+        rc = allow_stage_lds(reinterpret_cast<const void*>(ks));
+        if (rc != BRACE_OK)
+            return rc;
+        hipLaunchKernelGGL(ks, dim3((unsigned)sgrid), dim3(kBlock), kStageBytes, stream, updates, a,
+                           op, stage);
+        return check_launch("staged vote kernel");
+    }
     stream_kernel_t<VoteOp> k;
     switch (v) {
     case 4: k = brace_vote_pick_v4(sh.cols, sh.unroll, t.nontemporal, t.pipeline,
@@ -521,6 +593,19 @@ int launch_sum(const float* updates, int64_t n, int64_t d, int64_t ld, double sc
     if (grid > 0x7fffffffLL)
         return fail(BRACE_ERANGE, "range needs %lld blocks, more than one launch can hold",
                     (long long)grid);
+    const int64_t slots = (a.hi_a - a.lo_a) / (64 * (int64_t)v);
+    const int stage = stage_tiles_for(t, sh, v, slots, out, nullptr);
+    if (stage > 0) {
+        const int64_t per_block = (int64_t)stage * kWaves * kStageCols;
+        const int64_t sgrid = (slots + per_block - 1) / per_block + a.edge_blocks;
+        stream_staged_kernel_t<SumOp> ks = brace_sum_pick_staged(v, t.pipeline);
+        const int rcs = allow_stage_lds(reinterpret_cast<const void*>(ks));
+        if (rcs != BRACE_OK)
+            return rcs;
+        hipLaunchKernelGGL(ks, dim3((unsigned)sgrid), dim3(kBlock), kStageBytes, stream, updates, a,
+                           op, stage);
+        return check_launch("staged sum kernel");
+    }
     stream_kernel_t<SumOp> k;
     switch (v) {
     case 4: k = brace_sum_pick_v4(sh.cols, sh.unroll, t.nontemporal, t.pipeline,
@@ -959,9 +1044,9 @@ int brace_set_tuning(const brace_tuning_t* tuning)
     if (!(v == 0 || v == 1 || v == 2 || v == 4) ||
         !(c == 0 || c == 1 || c == 2 || c == 4 || c == 8) ||
         !(u == 0 || u == 2 || u == 4 || u == 8) || tuning->split_writes < 0 || tuning->split_writes > 2 || tuning->rowsplit < 0 ||
-        tuning->rowsplit > 2)
+        tuning->rowsplit > 2 || tuning->stage_writes < 0 || tuning->stage_writes > 2)
         return fail(BRACE_EINVAL, "tuning: vec in {0,1,2,4}, cols in {0,1,2,4,8}, unroll in {0,2,4,8}, "
-                    "split_writes and rowsplit in {0,1,2}");
+                    "split_writes, rowsplit and stage_writes in {0,1,2}");
     g_tuning = *tuning;
     return BRACE_OK;
 }

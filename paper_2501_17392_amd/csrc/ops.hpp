@@ -140,6 +140,23 @@ struct VoteOp {
         if (bits)
             atomicAnd(&bits[k >> 5], ~(1u << (k & 31)));
     }
+
+    // Staged variant (float result and / or in-place model update only; no bits, no sums).
+    __device__ __forceinline__ float stage_value(const State& st, int n) const
+    {
+        return decide(sign_sum(st, n));
+    }
+
+    __device__ __forceinline__ void flush4(int64_t k, f32x4 v) const
+    {
+        if (out)
+            __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(out + k));
+        if (w) {
+            f32x4 wv = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(w + k));
+            wv -= eta * v;
+            __builtin_nontemporal_store(wv, reinterpret_cast<f32x4*>(w + k));
+        }
+    }
 };
 
 struct SumOp {
@@ -171,11 +188,23 @@ struct SumOp {
     }
 
     __device__ __forceinline__ void pad_edge(int64_t) const {}
+
+    __device__ __forceinline__ float stage_value(const State& st, int) const
+    {
+        return (float)(st.acc * scale);
+    }
+
+    __device__ __forceinline__ void flush4(int64_t k, f32x4 v) const
+    {
+        __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(out + k));
+    }
 };
 
 }  // namespace brace_dev
 
 // One translation unit per (op, load width) instantiates its share of the kernels.
+brace_dev::stream_staged_kernel_t<brace_dev::VoteOp> brace_vote_pick_staged(int v, int pipe);
+brace_dev::stream_staged_kernel_t<brace_dev::SumOp> brace_sum_pick_staged(int v, int pipe);
 brace_dev::stream_kernel_t<brace_dev::VoteOp> brace_vote_pick_v1(int cols, int ru, int nt, int pipe,
                                                                  int rs);
 brace_dev::stream_kernel_t<brace_dev::VoteOp> brace_vote_pick_v2(int cols, int ru, int nt, int pipe,

@@ -64,7 +64,7 @@ def test_struct_layouts_match_the_header():
     assert B.BraceParams.ld.offset == 16
     assert B.BraceParams.out_bits_dev.offset == 24
     assert B.BraceParams.sums_dev.offset == 32
-    assert ctypes.sizeof(B.BraceTuning) == 32
+    assert ctypes.sizeof(B.BraceTuning) == 36
 
 
 def test_params_init_defaults(L):
@@ -240,11 +240,14 @@ def test_tuning_roundtrip_and_validation(L):
     B.brace_reset_tuning()
     base = B.brace_get_tuning()
     assert set(base) == {"vec", "cols", "unroll", "nontemporal", "pipeline", "split_writes",
-                         "rowsplit"}
+                         "rowsplit", "stage_writes"}
     B.brace_set_tuning(vec=2, cols=4, unroll=8, nontemporal=0, pipeline=0, split_writes=2,
-                       rowsplit=2)
+                       rowsplit=2, stage_writes=1)
     assert B.brace_get_tuning() == {"vec": 2, "cols": 4, "unroll": 8, "nontemporal": 0,
-                                    "pipeline": 0, "split_writes": 2, "rowsplit": 2}
+                                    "pipeline": 0, "split_writes": 2, "rowsplit": 2,
+                                    "stage_writes": 1}
+    with pytest.raises(B.BraceError):
+        B.brace_set_tuning(stage_writes=3)
     with pytest.raises(B.BraceError):
         B.brace_set_tuning(rowsplit=3)
     with pytest.raises(B.BraceError):

@@ -166,6 +166,26 @@ def test_padding_never_leaks_into_the_result():
     assert np.array_equal(g[32: 32 + d], O.brace_direct(upd.cpu().numpy(), 0.0).out)
 
 
+@pytest.mark.parametrize("n,d", [(5, 1024), (7, 8192 * 3 + 5), (12, 100_003), (100, 40_000)])
+def test_staged_float_output_forced(n, d):
+    # float-only output through the LDS-staged kernel (no bits, no sums, writes not split)
+    upd = special_matrix(n, d, seed=n + d)
+    host = upd.cpu().numpy()
+    try:
+        B.brace_set_tuning(split_writes=1, stage_writes=2)
+        for lam, rule in ((2.0, 0), (0.0, 1)):
+            guard = torch.full((d + 64,), 3.0, device=DEV, dtype=torch.float32)
+            out = guard[32: 32 + d]
+            B.brace_aggregate(upd, 0, lam, out=out, rule=rule)
+            torch.cuda.synchronize()
+            g = guard.cpu().numpy()
+            want = O.signsgd_majority(host) if rule else O.brace_direct(host, lam).out
+            assert np.array_equal(g[32: 32 + d], want)
+            assert (g[:32] == 3.0).all() and (g[32 + d:] == 3.0).all()
+    finally:
+        B.brace_reset_tuning()
+
+
 def test_majority_rule_three_valued():
     # signSGD's plain majority over the same four phases: ties stay at 0.
     for n, d in ((4, 5000), (7, 3001), (10, 70_001)):

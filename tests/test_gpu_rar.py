@@ -186,3 +186,36 @@ def test_large_workloads_full(idx, col_tile):
         print(f"{w.name}: mean over columns [{k0}, {k1}) matches", flush=True)
     del upd
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("n,d,ld,offset", [(3, 64, None, 0), (5, 257, None, 0), (7, 8192, None, 0),
+                                           (7, 8193, None, 0), (10, 40_000, None, 0),
+                                           (33, 70_001, None, 0), (8, 50_000, 50_002, 0),
+                                           (8, 50_000, 50_001, 0), (9, 123_456, None, 2),
+                                           (20, 300_007, None, 0)])
+def test_staged_burst_writes_forced(n, d, ld, offset):
+    # The LDS-staged kernel (one contiguous burst per block) forced on small and ragged inputs.
+    upd = device_matrix(n, d, seed=n * 3 + d, ld=ld, offset=offset)
+    host = upd.cpu().numpy()
+    try:
+        B.brace_set_tuning(stage_writes=2)
+        guard = torch.full((d + 64,), 3.0, device=DEV, dtype=torch.float32)
+        out = guard[32: 32 + d]
+        B.brace_rar_aggregate(upd, out)
+        torch.cuda.synchronize()
+        g = guard.cpu().numpy()
+        assert close(g[32: 32 + d], O.rar_sum_direct(host))
+        assert (g[:32] == 3.0).all() and (g[32 + d:] == 3.0).all()
+        B.brace_set_tuning(stage_writes=1)
+        ref = torch.empty(d, device=DEV, dtype=torch.float32)
+        B.brace_rar_aggregate(upd, ref)
+        torch.cuda.synchronize()
+        assert np.array_equal(ref.cpu().numpy(), g[32: 32 + d])     # same row order: bitwise equal
+        parts = torch.full((d,), 7.0, device=DEV, dtype=torch.float32)
+        B.brace_set_tuning(stage_writes=2)
+        for c in range(n):
+            B.brace_rar_aggregate(upd, parts, chunk=c)
+        torch.cuda.synchronize()
+        assert np.array_equal(parts.cpu().numpy(), g[32: 32 + d])
+    finally:
+        B.brace_reset_tuning()

@@ -56,10 +56,11 @@ def test_fused_update_small_shapes(n, d, offset, woff):
     host = upd.cpu().numpy()
     rng = np.random.default_rng(d)
     w0 = rng.standard_normal(d).astype(np.float32)
-    for lam, eta, split in ((2.0, 0.01, 0), (0.0, 0.5, 2), (-1.0, 1e-3, 2)):
+    for lam, eta, split, stage in ((2.0, 0.01, 0, 0), (0.0, 0.5, 2, 1), (-1.0, 1e-3, 2, 2),
+                                   (1.0, 0.25, 1, 2)):
         agg = O.brace_direct(host, lam).out
         try:
-            B.brace_set_tuning(split_writes=split)
+            B.brace_set_tuning(split_writes=split, stage_writes=stage)
             for with_bits in (False, True):
                 guard = torch.full((d + 16 + woff,), 5.0, device=DEV, dtype=torch.float32)
                 w = guard[8 + woff: 8 + woff + d]
