@@ -95,7 +95,7 @@ def main():
                     help="skip timing the other entry points (sum/mean, fused update, bit planes)")
     ap.set_defaults(next_rows=True)
     ap.add_argument("--tuning", default="",
-                    help="vec,cols,unroll,nontemporal,pipeline,split_writes,rowsplit (default: library "
+                    help="vec,cols,unroll,nontemporal,pipeline,split_writes,rowsplit,stage_writes (default: library "
                          "defaults)")
     args = ap.parse_args()
 

@@ -76,9 +76,81 @@ brace_quantize_kernel(const float* __restrict__ updates, int64_t ld, int64_t d,
         o[1] = (uint32_t)mine_n;
         o[2] = (uint32_t)(mine_p >> 32);
         o[3] = (uint32_t)(mine_n >> 32);
-        // streaming store: measured 1.84 ms against 2.07 ms with a plain store at n = 100, d = 25 M
+        // streaming store: 11 % faster than a plain store at n = 100, d = 25 M
         __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(signs + row * ld_words + 2 * pair));
     }
+}
+
+constexpr int kQuantBlock = 1024;           // 16 waves: enough loads in flight with one block per CU
+constexpr int kQuantWaves = kQuantBlock / 64;
+constexpr int kQuantGroup = 128;            // spans per block: 128 KiB of planes, one burst
+
+// The same for long rows, with the stores gathered: a block owns 128 adjacent spans of one
+// row; its 16 waves take them 16 at a time and park the planes in LDS, and the block then
+// writes its 128 KiB as one contiguous burst.  Measured at n = 100, d = 25 M on one device:
+// 1.85 ms with a store per span, 1.72 ms with the bursts, 1.40 ms for the reads alone.
+__global__ void __launch_bounds__(kQuantBlock)
+brace_quantize_staged_kernel(const float* __restrict__ updates, int64_t ld, int64_t d,
+                      uint32_t* __restrict__ signs, int64_t ld_words, int64_t groups_per_row)
+{
+    extern __shared__ unsigned char lds_raw[];
+    u32x4* stage = reinterpret_cast<u32x4*>(lds_raw);           // kQuantGroup x 64 entries
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int64_t row = (int64_t)blockIdx.x / groups_per_row;
+    const int64_t span0 = ((int64_t)blockIdx.x % groups_per_row) * kQuantGroup;
+    const int64_t spans = (d + kQuantSpan - 1) / kQuantSpan;    // per row
+    const float* rowp = updates + row * ld;
+    for (int it = 0; it < kQuantGroup / kQuantWaves; ++it) {
+        const int local = it * kQuantWaves + wave;
+        const int64_t span = span0 + local;
+        if (span >= spans)
+            break;                                              // wave-uniform; barrier is below
+        const int64_t k0 = span * kQuantSpan;
+        const float* src = rowp + k0;
+        const bool full = k0 + kQuantSpan <= d;
+        unsigned long long mine_p = 0, mine_n = 0;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            float x[16];
+            if (full) {
+#pragma unroll
+                for (int u = 0; u < 16; ++u)
+                    x[u] = __builtin_nontemporal_load(src + (16 * b + u) * 64 + lane);
+            } else {
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    const int64_t k = k0 + (16 * b + u) * 64 + lane;
+                    x[u] = (k < d) ? src[(16 * b + u) * 64 + lane] : 0.0f;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const unsigned long long mp = __ballot(x[u] > 0.0f);
+                const unsigned long long mn = __ballot(x[u] < 0.0f);
+                if (lane == 16 * b + u) {
+                    mine_p = mp;
+                    mine_n = mn;
+                }
+            }
+        }
+        u32x4 o;
+        o[0] = (uint32_t)mine_p;
+        o[1] = (uint32_t)mine_n;
+        o[2] = (uint32_t)(mine_p >> 32);
+        o[3] = (uint32_t)(mine_n >> 32);
+        stage[local * 64 + lane] = o;           // lane's two word pairs: coordinates k0 + 64*lane ..
+    }
+    __syncthreads();
+    // Entry e of the group = word pairs 2e, 2e+1 counted from the group's first pair.
+    const int64_t pairs = (d + 31) / 32 + (((d + 31) / 32) & 1);   // per row, padded to even
+    const int64_t pair0 = span0 * (kQuantSpan / 32);
+    u32x4* dst = reinterpret_cast<u32x4*>(signs + row * ld_words + 2 * pair0);
+    int64_t entries = (pairs - pair0) / 2;
+    if (entries > (int64_t)kQuantGroup * 64)
+        entries = (int64_t)kQuantGroup * 64;
+    for (int64_t e = threadIdx.x; e < entries; e += kQuantBlock)
+        __builtin_nontemporal_store(stage[e], dst + e);
 }
 
 // (h, l) <- a + b + c on 32 independent 1-bit lanes per component (carry-save adder).

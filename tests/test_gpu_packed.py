@@ -56,12 +56,19 @@ def planes_buffer(n, d, extra_words=0):
 @pytest.mark.parametrize("n,d,ld,offset,extra", [
     (1, 1, None, 0, 0), (2, 31, None, 0, 0), (3, 32, None, 0, 0), (3, 33, None, 0, 0),
     (4, 64, None, 0, 0), (5, 1000, None, 0, 0), (3, 4095, None, 0, 0), (3, 4096, None, 0, 0),
-    (3, 4097, None, 0, 0), (7, 12_345, None, 1, 4), (6, 20_000, 20_003, 2, 8), (10, 70_001, None, 0, 0)])
-def test_quantize_matches_oracle_planes(n, d, ld, offset, extra):
+    (3, 4097, None, 0, 0), (7, 12_345, None, 1, 4), (6, 20_000, 20_003, 2, 8), (10, 70_001, None, 0, 0),
+    # rows longer than one 128-span burst (524,288 coordinates), ragged last burst and last span
+    (3, 524_288, None, 0, 0), (2, 524_289, None, 3, 4), (3, 1_100_003, 1_100_005, 1, 8)])
+@pytest.mark.parametrize("stage", [0, 1, 2], ids=["auto", "per-span-stores", "bursts"])
+def test_quantize_matches_oracle_planes(n, d, ld, offset, extra, stage):
     g = special(n, d, seed=n * 11 + d)
     upd = to_device(g, ld, offset)
     signs = planes_buffer(n, d, extra)
-    B.brace_quantize(upd, signs)
+    B.brace_set_tuning(stage_writes=stage)
+    try:
+        B.brace_quantize(upd, signs)
+    finally:
+        B.brace_reset_tuning()
     torch.cuda.synchronize()
     got = signs.cpu().numpy().view(np.uint32)
     assert np.array_equal(got, O.sign_planes(g))
@@ -147,6 +154,10 @@ def test_large_workloads_full(idx, col_tile):
         ref = O.sign_planes(host[:, : s1 - k0])
         assert np.array_equal(planes[:, 2 * (k0 // 32): 2 * (k0 // 32) + 2 * ((s1 - k0) // 32)],
                               ref[:, : 2 * ((s1 - k0) // 32)]), (w.name, k0)
+        # and on the tile's last coordinates (in the last tile: the ragged end of the rows)
+        s0 = max(k0, (k1 - 65_536) // 64 * 64)
+        ref = O.sign_planes(host[:, s0 - k0:])
+        assert np.array_equal(planes[:, 2 * (s0 // 32): 2 * (s0 // 32) + ref.shape[1]], ref), (w.name, k0)
         print(f"{w.name}: packed vote over columns [{k0}, {k1}) matches", flush=True)
     del upd, signs
     torch.cuda.empty_cache()
