@@ -49,19 +49,26 @@ brace_tuning_t default_tuning()
     return t;
 }
 
-// Compute units of the current device (0 if it cannot be queried); cached per process.
+constexpr int kMaxDevices = 64;            // per-device caches; devices beyond are queried every call
+
+// Compute units of the current device (0 if it cannot be queried); cached per device.
 int compute_units()
 {
-    static int cached = -1;
-    if (cached < 0) {
-        int dev = 0, cu = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
-            cached = cu;
-        else
-            cached = 0;
+    static int cached[kMaxDevices] = {};   // 0 = not known yet
+    int dev = 0, cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return 0;
     }
-    return cached;
+    if (dev >= 0 && dev < kMaxDevices && cached[dev] > 0)
+        return cached[dev];
+    if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return 0;
+    }
+    if (dev >= 0 && dev < kMaxDevices)
+        cached[dev] = cu;
+    return cu;
 }
 
 brace_tuning_t g_tuning = default_tuning();
@@ -443,12 +450,18 @@ int stage_tiles_for(const brace_tuning_t& t, const Shape& sh, int v, int64_t slo
     return best;
 }
 
-// Opt a kernel in to more than the default 64 KiB of dynamic LDS (once per kernel).
+// Opt a kernel in to more than the default 64 KiB of dynamic LDS (once per kernel and device).
 int allow_stage_lds(const void* kernel)
 {
-    static const void* done[16] = {};
-    for (const void* k : done)
-        if (k == kernel)
+    struct Seen { const void* kernel; int dev; };
+    static Seen done[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(BRACE_EHIP, "no current device");
+    }
+    for (const Seen& s : done)
+        if (s.kernel == kernel && s.dev == dev)
             return BRACE_OK;
     const hipError_t err = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                                (int)kStageBytes);
@@ -457,9 +470,10 @@ int allow_stage_lds(const void* kernel)
         return fail(BRACE_EHIP, "cannot reserve %zu bytes of LDS: %s", kStageBytes,
                     hipGetErrorString(err));
     }
-    for (const void*& k : done)
-        if (!k) {
-            k = kernel;
+    for (Seen& s : done)
+        if (!s.kernel) {           // a full table only means the attribute is set again next time
+            s.kernel = kernel;
+            s.dev = dev;
             break;
         }
     return BRACE_OK;
@@ -888,6 +902,14 @@ int brace_quantize(const float* updates_dev, int64_t n, int64_t d, int64_t ld,
     if (!updates_dev || !signs_dev || !aligned_to(updates_dev, 4) || !aligned_to(signs_dev, 16))
         return fail(BRACE_EINVAL, "updates_dev (4-byte aligned) and signs_dev (16-byte aligned) "
                                   "must be non-NULL");
+    {
+        const char* in_lo = reinterpret_cast<const char*>(updates_dev);
+        const char* in_hi = in_lo + ((n - 1) * ld + d) * 4;
+        const char* out_lo = reinterpret_cast<const char*>(signs_dev);
+        const char* out_hi = out_lo + ((n - 1) * ld_words + brace_packed_row_words(d)) * 4;
+        if (out_lo < in_hi && in_lo < out_hi)
+            return fail(BRACE_EINVAL, "signs_dev overlaps updates_dev");
+    }
     int rc = check_device_range(updates_dev, ((n - 1) * ld + d) * 4, "updates_dev");
     if (rc == BRACE_OK)
         rc = check_device_range(signs_dev, ((n - 1) * ld_words + brace_packed_row_words(d)) * 4,

@@ -198,6 +198,8 @@ def test_packed_entry_points_validate(L):
     assert L.brace_quantize(FAKE_IN, 4, 100, 0, FAKE_OUT, 4, None) == E           # pitch too small
     assert L.brace_quantize(FAKE_IN, 4, 100, 0, FAKE_OUT, 10, None) == E          # not a multiple of 4
     assert L.brace_quantize(FAKE_IN, 0, 100, 0, FAKE_OUT, 0, None) == E
+    assert L.brace_quantize(FAKE_IN, 4, 100, 0, FAKE_IN + 64, 0, None) == E       # planes inside the matrix
+    assert b"overlaps" in L.brace_last_error()
     assert L.brace_quantize(FAKE_IN, B.BRACE_MAX_CLIENTS + 1, 100, 0, FAKE_OUT, 0, None) == R
     assert L.brace_quantize(None, 4, 0, 0, None, 0, None) == B.BRACE_OK
     assert L.brace_vote_packed(FAKE_IN, 4, 100, 0, 1, None, FAKE_OUT, None) == E
