@@ -153,19 +153,38 @@ brace_quantize_staged_kernel(const float* __restrict__ updates, int64_t ld, int6
         __builtin_nontemporal_store(stage[e], dst + e);
 }
 
-// (h, l) <- a + b + c on 32 independent 1-bit lanes per component (carry-save adder).
+// (h, l) <- a + b + c on 32 independent 1-bit lanes per component (carry-save adder):
+// parity and majority, each one three-input bit operation on gfx950 (truth tables 0x96, 0xE8;
+// both are symmetric in their inputs).
 __device__ __forceinline__ void csa(u32x4& h, u32x4& l, const u32x4 a, const u32x4 b, const u32x4 c)
 {
-    const u32x4 u = a ^ b;
-    h = (a & b) | (u & c);
-    l = u ^ c;
+    u32x4 maj, par;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        par[e] = __builtin_amdgcn_bitop3_b32(a[e], b[e], c[e], 0x96);
+        maj[e] = __builtin_amdgcn_bitop3_b32(a[e], b[e], c[e], 0xE8);
+    }
+    l = par;
+    h = maj;
+}
+
+// Pins a wave-uniform pointer to scalar registers, so that loads through it take the
+// "scalar base + 32-bit lane offset" form and need no per-lane 64-bit address registers.
+template <class T>
+__device__ __forceinline__ const T* scalar_ptr(const T* q)
+{
+    const uint64_t v = reinterpret_cast<uint64_t>(q);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const T*>(((uint64_t)hi << 32) | lo);
 }
 
 // Phases II-IV on the planes.  One lane owns two adjacent word pairs (64 coordinates):
 // component 0/1 = positive/negative plane of the first pair, 2/3 of the second.
 // cnt[b] is bit b of the four running counts.  Eight clients are folded at a time through
 // a carry-save tree (ones -> twos -> fours -> eights), and only the "eights" word ripples
-// into the higher counter bits.
+// into the higher counter bits.  (Measured and dropped: requesting the next rows before
+// folding the current ones; the kernel is bound by the memory system either way.)
 // The decision S >= thresh is taken on the slices as X - Y - c >= 0 with X = pos & mask_p,
 // Y = neg & mask_n and the constant c chosen by the host for the zero_sign in force.
 template <int B>
@@ -182,13 +201,16 @@ brace_vote_packed_kernel(const u32x4* __restrict__ signs, int64_t ld4, int n, in
     for (int b = 0; b < B; ++b)
         cnt[b] = (u32x4)(0u);
 
-    const u32x4* p = signs + col;
+    // wave-uniform row pointer + lane offset: row stepping stays in scalar registers
+    const uint32_t lane = threadIdx.x & 63;
+    const int64_t col0 = __builtin_amdgcn_readfirstlane((int)((col - lane) >> 6)) * (int64_t)64;
+    const u32x4* p = signs + col0;
     int i = 0;
     for (; i + 8 <= n; i += 8) {
         u32x4 a[8];
 #pragma unroll
         for (int r = 0; r < 8; ++r)
-            a[r] = __builtin_nontemporal_load(p + (int64_t)r * ld4);
+            a[r] = __builtin_nontemporal_load(scalar_ptr(p + (int64_t)r * ld4) + lane);
         __builtin_amdgcn_sched_barrier(0);
         u32x4 twos_a, twos_b, fours_a, fours_b, eights;
         csa(twos_a, cnt[0], cnt[0], a[0], a[1]);
@@ -208,7 +230,7 @@ brace_vote_packed_kernel(const u32x4* __restrict__ signs, int64_t ld4, int n, in
         p += 8 * ld4;
     }
     for (; i < n; ++i) {
-        u32x4 carry = *p;
+        u32x4 carry = scalar_ptr(p)[lane];
 #pragma unroll
         for (int b = 0; b < B; ++b) {
             const u32x4 t = cnt[b] & carry;
