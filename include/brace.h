@@ -208,8 +208,9 @@ typedef struct brace_tuning {
     int32_t  rowsplit;     /* the 4 waves of a block share their columns and split the client     */
                            /* rows (partial results meet in LDS): 0 = for short ranges (default), */
                            /* 1 = never, 2 = always                                               */
-    int32_t  stage_writes; /* results with no compact form (sum / mean, in-place update) are      */
-                           /* parked in LDS and written as one 128 KiB burst per block:           */
+    int32_t  stage_writes; /* results with no compact form (sum / mean, in-place update, the bit   */
+                           /* planes of brace_quantize) are parked in LDS and written as one      */
+                           /* 128 KiB burst per block:                                            */
                            /* 0 = for large ranges (default), 1 = never, 2 = whenever possible    */
 } brace_tuning_t;
 
