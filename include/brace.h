@@ -155,12 +155,24 @@ int brace_apply_bits(const void* bits_dev, int64_t d, float eta, float* w_dev, v
  * signs_dev must be 16-byte aligned and must not overlap updates_dev.  brace_vote_packed honours lambda, zero_sign and
  * out_bits_dev of params (params->ld is ignored, sums_dev must be NULL); out_dev must be
  * 16-byte aligned and may be NULL when out_bits_dev is given.
+ *
+ * The _chunk / _chunks forms vote one ring chunk c, or the run [chunk_begin, chunk_end), of
+ * the Sec. 2.2 partition (brace_chunk_range) and write only out_dev[lo .. hi) and the bits of
+ * those coordinates (merged atomically into words shared with a neighbouring chunk; the caller
+ * clears the bit array once).  out_dev / out_bits_dev are still the full-length vectors.  This is
+ * what one device of a sharded run executes on the planes it received for its chunks.
  */
 int64_t brace_packed_row_words(int64_t d);
 int brace_quantize(const float* updates_dev, int64_t n, int64_t d, int64_t ld,
                    uint32_t* signs_dev, int64_t ld_words, void* hip_stream);
 int brace_vote_packed(const uint32_t* signs_dev, int64_t n, int64_t d, int64_t ld_words, int64_t f,
                       const brace_params_t* params, float* out_dev, void* hip_stream);
+int brace_vote_packed_chunk(const uint32_t* signs_dev, int64_t n, int64_t d, int64_t ld_words,
+                            int64_t f, int64_t chunk, const brace_params_t* params, float* out_dev,
+                            void* hip_stream);
+int brace_vote_packed_chunks(const uint32_t* signs_dev, int64_t n, int64_t d, int64_t ld_words,
+                             int64_t f, int64_t chunk_begin, int64_t chunk_end,
+                             const brace_params_t* params, float* out_dev, void* hip_stream);
 
 /*
  * The operation BRACE replaces: plain ring-all-reduce aggregation (Sec. 2.2), out[k] =

@@ -66,7 +66,8 @@ EXPORTS = (
     "brace_chunk_owner", "brace_last_error", "brace_set_tuning", "brace_get_tuning",
     "brace_probe_read", "brace_probe_copy", "brace_rar_aggregate", "brace_rar_aggregate_chunk",
     "brace_aggregate_update", "brace_aggregate_update_chunk", "brace_expand_bits", "brace_apply_bits",
-    "brace_packed_row_words", "brace_quantize", "brace_vote_packed", "brace_aggregate_chunks",
+    "brace_packed_row_words", "brace_quantize", "brace_vote_packed", "brace_vote_packed_chunk",
+    "brace_vote_packed_chunks", "brace_aggregate_chunks",
     "brace_set_pointer_checks",
 )
 
@@ -125,6 +126,10 @@ def lib():
     L.brace_quantize.restype = ctypes.c_int
     L.brace_vote_packed.argtypes = [vp, i64, i64, i64, i64, pp, vp, vp]
     L.brace_vote_packed.restype = ctypes.c_int
+    L.brace_vote_packed_chunk.argtypes = [vp, i64, i64, i64, i64, i64, pp, vp, vp]
+    L.brace_vote_packed_chunk.restype = ctypes.c_int
+    L.brace_vote_packed_chunks.argtypes = [vp, i64, i64, i64, i64, i64, i64, pp, vp, vp]
+    L.brace_vote_packed_chunks.restype = ctypes.c_int
     L.brace_set_pointer_checks.argtypes = [ctypes.c_int32]
     L.brace_set_pointer_checks.restype = ctypes.c_int
     rp = ctypes.POINTER(BraceRarParams)
@@ -309,6 +314,29 @@ def brace_vote_packed(signs, d: int, f: int, lam: float = 5.0, zero_sign: int = 
     p = make_params(lam, zero_sign, 0, _ptr(out_bits), None)
     _check(lib().brace_vote_packed(signs.data_ptr(), n, d, ld_words, f, ctypes.byref(p), _ptr(out),
                                    _stream_handle(stream)))
+    return out
+
+
+def brace_vote_packed_chunk(signs, d: int, f: int, chunk: int, lam: float = 5.0, zero_sign: int = 0,
+                            out=None, out_bits=None, stream=None):
+    """brace_vote_packed for one ring chunk; `out` / `out_bits` are the FULL vectors."""
+    n = signs.shape[0]
+    ld_words = signs.stride(0) if n > 1 else 0
+    p = make_params(lam, zero_sign, 0, _ptr(out_bits), None)
+    _check(lib().brace_vote_packed_chunk(signs.data_ptr(), n, d, ld_words, f, chunk, ctypes.byref(p),
+                                         _ptr(out), _stream_handle(stream)))
+    return out
+
+
+def brace_vote_packed_chunks(signs, d: int, f: int, chunk_begin: int, chunk_end: int,
+                             lam: float = 5.0, zero_sign: int = 0, out=None, out_bits=None,
+                             stream=None):
+    """brace_vote_packed for a run of consecutive ring chunks in one call."""
+    n = signs.shape[0]
+    ld_words = signs.stride(0) if n > 1 else 0
+    p = make_params(lam, zero_sign, 0, _ptr(out_bits), None)
+    _check(lib().brace_vote_packed_chunks(signs.data_ptr(), n, d, ld_words, f, chunk_begin, chunk_end,
+                                          ctypes.byref(p), _ptr(out), _stream_handle(stream)))
     return out
 
 

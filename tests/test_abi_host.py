@@ -211,6 +211,17 @@ def test_packed_entry_points_validate(L):
     with_sums = B.make_params(sums_ptr=FAKE_OUT)
     assert L.brace_vote_packed(FAKE_IN, 4, 100, 0, 1, ctypes.byref(with_sums), FAKE_OUT, None) == E
     assert L.brace_vote_packed(None, 4, 0, 0, 1, pr, None, None) == B.BRACE_OK
+    # chunk forms: the same checks plus the chunk index
+    assert L.brace_vote_packed_chunk(FAKE_IN, 4, 100, 0, 1, 4, pr, FAKE_OUT, None) == R
+    assert L.brace_vote_packed_chunk(FAKE_IN, 4, 100, 0, 1, -1, pr, FAKE_OUT, None) == R
+    assert L.brace_vote_packed_chunk(None, 4, 100, 0, 1, 0, pr, FAKE_OUT, None) == E
+    assert L.brace_vote_packed_chunk(FAKE_IN, 4, 100, 0, 1, 0, None, FAKE_OUT, None) == E
+    assert L.brace_vote_packed_chunks(FAKE_IN, 4, 100, 0, 1, 2, 1, pr, FAKE_OUT, None) == R
+    assert L.brace_vote_packed_chunks(FAKE_IN, 4, 100, 0, 1, 0, 5, pr, FAKE_OUT, None) == R
+    assert L.brace_vote_packed_chunks(FAKE_IN, 0, 100, 0, 0, 0, 0, pr, FAKE_OUT, None) == E
+    assert L.brace_vote_packed_chunks(FAKE_IN, 4, 100, 0, 9, 0, 4, pr, FAKE_OUT, None) == E   # f > n
+    assert L.brace_vote_packed_chunks(None, 4, 100, 0, 1, 2, 2, pr, None, None) == B.BRACE_OK  # empty run
+    assert L.brace_vote_packed_chunk(None, 8, 3, 0, 1, 5, pr, None, None) == B.BRACE_OK        # empty chunk (d < n)
 
 
 def test_rar_aggregate_rejects_invalid_arguments(L):

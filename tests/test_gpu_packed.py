@@ -130,6 +130,62 @@ def test_quantize_then_vote_equals_float_path_small_workloads():
         assert np.array_equal(out.cpu().numpy(), O.brace_direct(host, 5.0).out)
 
 
+@pytest.mark.parametrize("n,d", [(3, 3), (7, 3), (5, 1024), (10, 10_000), (20, 100_003), (13, 4096),
+                                 (6, 70_001), (37, 300_007), (100, 250_000)])
+def test_packed_chunks_tile_the_whole(n, d):
+    """Chunk by chunk (in a scrambled order), as runs of chunks, and whole: the same vector."""
+    g = special(n, d, seed=n + d)
+    upd = to_device(g)
+    signs = planes_buffer(n, d)
+    B.brace_quantize(upd, signs)
+    for lam, zs in ((1.0, 0), (0.0, 1), (-2.0, -1)):
+        want = O.brace_direct(g, lam, zs)
+        nwords = (d + 31) // 32
+        out = torch.full((d,), 7.0, device=DEV, dtype=torch.float32)
+        bits = torch.zeros(nwords, device=DEV, dtype=torch.int32)
+        for c in np.random.default_rng(n).permutation(n):
+            B.brace_vote_packed_chunk(signs, d, 0, int(c), lam, zs, out=out, out_bits=bits)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), want.out), (n, d, lam, zs)
+        got_bits = bits.cpu().numpy().view(np.uint8)
+        assert np.array_equal(got_bits[: (d + 7) // 8], want.bits)
+        assert not got_bits[(d + 7) // 8:].any()
+        # floats only (bit-words parked in `out`), as three runs of chunks
+        out2 = torch.full((d,), 7.0, device=DEV, dtype=torch.float32)
+        cuts = sorted({0, n // 3, (2 * n) // 3, n})
+        for a, b in zip(cuts[:-1], cuts[1:]):
+            B.brace_vote_packed_chunks(signs, d, 0, a, b, lam, zs, out=out2)
+        torch.cuda.synchronize()
+        assert np.array_equal(out2.cpu().numpy(), want.out), (n, d, lam, zs)
+
+
+def test_packed_single_chunk_touches_only_its_range():
+    n, d = 9, 50_003
+    g = special(n, d, seed=77)
+    upd = to_device(g)
+    signs = planes_buffer(n, d)
+    B.brace_quantize(upd, signs)
+    want = O.brace_direct(g, 1.0)
+    for c in (0, 4, n - 1):
+        lo, hi = O.chunk_range(n, d, c)
+        guard = torch.full((d + 128,), 7.0, device=DEV, dtype=torch.float32)
+        out = guard[64: 64 + d]
+        bits = torch.zeros((d + 31) // 32, device=DEV, dtype=torch.int32)
+        B.brace_vote_packed_chunk(signs, d, 0, c, 1.0, out=out, out_bits=bits)
+        torch.cuda.synchronize()
+        h = guard.cpu().numpy()
+        assert np.array_equal(h[64 + lo: 64 + hi], want.out[lo:hi])
+        assert (h[: 64 + lo] == 7.0).all() and (h[64 + hi:] == 7.0).all()
+        unpacked = np.unpackbits(bits.cpu().numpy().view(np.uint8), bitorder="little")
+        assert np.array_equal(unpacked[lo:hi], (want.out[lo:hi] > 0).astype(np.uint8))
+        assert not unpacked[:lo].any() and not unpacked[hi:].any()
+        # bits only
+        bits2 = torch.zeros((d + 31) // 32, device=DEV, dtype=torch.int32)
+        B.brace_vote_packed_chunk(signs, d, 0, c, 1.0, out_bits=bits2)
+        torch.cuda.synchronize()
+        assert torch.equal(bits, bits2)
+
+
 @pytest.mark.parametrize("idx,col_tile", [(2, 2_000_000), (3, 2_000_000), (4, 4_000_000)])
 def test_large_workloads_full(idx, col_tile):
     w = synth.WORKLOADS[idx]
@@ -139,8 +195,15 @@ def test_large_workloads_full(idx, col_tile):
     out = torch.empty(w.d, device=DEV, dtype=torch.float32)
     bits = torch.empty((w.d + 31) // 32, device=DEV, dtype=torch.int32)
     B.brace_vote_packed(signs, w.d, w.f, 5.0, out=out, out_bits=bits)
+    # the same through the chunk form: four runs of ring chunks, as four devices would vote them
+    out_runs = torch.empty(w.d, device=DEV, dtype=torch.float32)
+    cuts = [0, w.n // 4, w.n // 2, (3 * w.n) // 4, w.n]
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        B.brace_vote_packed_chunks(signs, w.d, w.f, a, b, 5.0, out=out_runs)
     torch.cuda.synchronize()
     got = out.cpu().numpy()
+    got_runs = out_runs.cpu().numpy()
+    del out_runs
     got_bits = bits.cpu().numpy().view(np.uint8)
     planes = signs.cpu().numpy().view(np.uint32)
     for k0 in range(0, w.d, col_tile):
@@ -148,6 +211,7 @@ def test_large_workloads_full(idx, col_tile):
         host = upd[:, k0:k1].contiguous().cpu().numpy()
         want, _, _ = C.brace_direct(host, 5.0, 0, want_sums=False, want_bits=False)
         assert np.array_equal(got[k0:k1], want), (w.name, k0)
+        assert np.array_equal(got_runs[k0:k1], want), (w.name, k0)
         assert np.array_equal(got_bits[k0 // 8: (k1 + 7) // 8], O.pack_bits(want)), (w.name, k0)
         # the planes themselves, on a slice of the tile (the numpy oracle is slow on 1e8 values)
         s1 = min(k1, k0 + 262_144)

@@ -240,6 +240,11 @@ def test_planes_random_case(seed):
     whole, out = guarded(d, 7.0, torch.float32)
     bits = torch.full(((d + 31) // 32,), -1, device=DEV, dtype=torch.int32)
     B.brace_vote_packed(signs, d, 0, lam, zs, out=out, out_bits=bits)
+    # a random run of chunks into buffers of its own
+    a, b, lo, hi = chunk_run(rng, n, d)
+    whole_c, out_c = guarded(d, 9.0, torch.float32)
+    bits_c = torch.zeros((d + 31) // 32, device=DEV, dtype=torch.int32) if rng.integers(0, 2) else None
+    B.brace_vote_packed_chunks(signs, d, 0, a, b, lam, zs, out=out_c, out_bits=bits_c)
     torch.cuda.synchronize()
     host = store.cpu().numpy()
     assert np.array_equal(host[:, :words].view(np.uint32), O.sign_planes(g)), tag
@@ -250,6 +255,14 @@ def test_planes_random_case(seed):
     unpacked = np.unpackbits(bits.cpu().numpy().view(np.uint8), bitorder="little")
     assert np.array_equal(unpacked[:d], (want.out > 0).astype(np.uint8)), tag
     assert not unpacked[d:].any(), tag
+    got_c = out_c.cpu().numpy()
+    assert np.array_equal(got_c[lo:hi], want.out[lo:hi]), (tag, a, b)
+    assert (got_c[:lo] == 9.0).all() and (got_c[hi:] == 9.0).all(), (tag, a, b)
+    assert untouched(whole_c, d, 9.0), (tag, a, b)
+    if bits_c is not None:
+        unpacked_c = np.unpackbits(bits_c.cpu().numpy().view(np.uint8), bitorder="little")
+        assert np.array_equal(unpacked_c[lo:hi], (want.out[lo:hi] > 0).astype(np.uint8)), (tag, a, b)
+        assert not unpacked_c[:lo].any() and not unpacked_c[hi:].any(), (tag, a, b)
     # receive side of Share-Only from those bits
     whole2, out2 = guarded(d, 3.0, torch.float32, 1)
     B.brace_expand_bits(bits, d, out2)
