@@ -175,6 +175,19 @@ int brace_vote_packed_chunks(const uint32_t* signs_dev, int64_t n, int64_t d, in
                              const brace_params_t* params, float* out_dev, void* hip_stream);
 
 /*
+ * Sec. 3 Phase III on its own, for an owner that holds partial sign-sums: in Share-Reduce
+ * (Phase II) what travels are partial sums of signs (m bits per dimension in the cost
+ * analysis of Sec. 3).  parts_dev[j][k], j in [0, g), are g such partial sums as int16 (row
+ * pitch ld elements, 0 = d), e.g. one per device; S[k] = sum_j parts[j][k] and Eq. (1) gives
+ * out_dev[k] = S[k] > lambda ? +1 : -1 and / or the packed bits (params->out_bits_dev, padding
+ * bits zero).  zero_sign of params is not used (the signs are already summed); rule must be 0
+ * and sums_dev NULL.  |S| must stay below 2^30 (g <= BRACE_MAX_CLIENTS guarantees it).
+ * 16-byte aligned parts_dev / out_dev with ld a multiple of 8 take the wide path.
+ */
+int brace_consensus_sums(const int16_t* parts_dev, int64_t g, int64_t d, int64_t ld,
+                         const brace_params_t* params, float* out_dev, void* hip_stream);
+
+/*
  * The operation BRACE replaces: plain ring-all-reduce aggregation (Sec. 2.2), out[k] =
  * sum_i updates[i][k], or the Mean rule of Sec. 2.1 (sum / n) with mean = 1.  Same streaming
  * shape and chunking as brace_aggregate.  Accumulation is in fp64 and the result is rounded

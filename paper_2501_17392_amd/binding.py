@@ -67,7 +67,7 @@ EXPORTS = (
     "brace_probe_read", "brace_probe_copy", "brace_rar_aggregate", "brace_rar_aggregate_chunk",
     "brace_aggregate_update", "brace_aggregate_update_chunk", "brace_expand_bits", "brace_apply_bits",
     "brace_packed_row_words", "brace_quantize", "brace_vote_packed", "brace_vote_packed_chunk",
-    "brace_vote_packed_chunks", "brace_aggregate_chunks",
+    "brace_vote_packed_chunks", "brace_aggregate_chunks", "brace_consensus_sums",
     "brace_set_pointer_checks",
 )
 
@@ -130,6 +130,8 @@ def lib():
     L.brace_vote_packed_chunk.restype = ctypes.c_int
     L.brace_vote_packed_chunks.argtypes = [vp, i64, i64, i64, i64, i64, i64, pp, vp, vp]
     L.brace_vote_packed_chunks.restype = ctypes.c_int
+    L.brace_consensus_sums.argtypes = [vp, i64, i64, i64, pp, vp, vp]
+    L.brace_consensus_sums.restype = ctypes.c_int
     L.brace_set_pointer_checks.argtypes = [ctypes.c_int32]
     L.brace_set_pointer_checks.restype = ctypes.c_int
     rp = ctypes.POINTER(BraceRarParams)
@@ -337,6 +339,18 @@ def brace_vote_packed_chunks(signs, d: int, f: int, chunk_begin: int, chunk_end:
     p = make_params(lam, zero_sign, 0, _ptr(out_bits), None)
     _check(lib().brace_vote_packed_chunks(signs.data_ptr(), n, d, ld_words, f, chunk_begin, chunk_end,
                                           ctypes.byref(p), _ptr(out), _stream_handle(stream)))
+    return out
+
+
+def brace_consensus_sums(parts, lam: float = 5.0, out=None, out_bits=None, stream=None):
+    """Phase III on (g, d) int16 partial sign-sums: Eq. (1) applied to their column sums."""
+    if parts.dim() != 2 or parts.stride(1) != 1 and parts.shape[1] > 1:
+        raise ValueError("parts must be (g, d) with unit column stride")
+    g, d = parts.shape
+    ld = parts.stride(0) if g > 1 else 0
+    p = make_params(lam, 0, 0, _ptr(out_bits), None)
+    _check(lib().brace_consensus_sums(_ptr(parts), g, d, ld, ctypes.byref(p), _ptr(out),
+                                      _stream_handle(stream)))
     return out
 
 

@@ -190,6 +190,92 @@ brace_packed_edge_kernel(const uint32_t* __restrict__ signs, int64_t ld_words, i
     }
 }
 
+// Sec. 3 Phase III on partial sign-sums: S[k] = sum_j parts[j][k] over the g partial sums an
+// owner has received, then Eq. (1).  One thread per 8 consecutive coordinates: a 16-byte load
+// per part, two 16-byte float stores and one byte of packed bits.
+typedef short i16x8 __attribute__((ext_vector_type(8)));
+
+__global__ void __launch_bounds__(kBlock)
+brace_consensus_kernel(const int16_t* __restrict__ parts, int64_t ld, int g, int64_t octets,
+                       int thresh, float* __restrict__ out, uint8_t* __restrict__ bits)
+{
+    const int64_t o = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (o >= octets)
+        return;
+    const int16_t* p = parts + 8 * o;
+    int s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    int j = 0;
+    for (; j + 4 <= g; j += 4) {
+        i16x8 v[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            v[r] = __builtin_nontemporal_load(reinterpret_cast<const i16x8*>(p + (int64_t)r * ld));
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                s[e] += v[r][e];
+        p += 4 * ld;
+    }
+    for (; j < g; ++j) {
+        const i16x8 v = *reinterpret_cast<const i16x8*>(p);
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            s[e] += v[e];
+        p += ld;
+    }
+    uint32_t byte = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        byte |= (s[e] >= thresh ? 1u : 0u) << e;
+    if (out) {
+        f32x4 a, b;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            a[e] = (byte >> e) & 1u ? 1.0f : -1.0f;
+            b[e] = (byte >> (e + 4)) & 1u ? 1.0f : -1.0f;
+        }
+        __builtin_nontemporal_store(a, reinterpret_cast<f32x4*>(out + 8 * o));
+        __builtin_nontemporal_store(b, reinterpret_cast<f32x4*>(out + 8 * o + 4));
+    }
+    if (bits)
+        bits[o] = (uint8_t)byte;
+}
+
+// The same one coordinate per thread for [lo, d): rows that are not 16-byte aligned, and the
+// last d mod 8 coordinates.  Every bit is set or cleared atomically (threads share words).
+__global__ void __launch_bounds__(kBlock)
+brace_consensus_tail_kernel(const int16_t* __restrict__ parts, int64_t ld, int g, int64_t lo,
+                            int64_t d, int thresh, float* __restrict__ out, uint32_t* bits)
+{
+    const int64_t k = lo + (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (k >= d)
+        return;
+    int s = 0;
+    const int16_t* p = parts + k;
+    for (int j = 0; j < g; ++j) {
+        s += *p;
+        p += ld;
+    }
+    const bool up = s >= thresh;
+    if (out)
+        out[k] = up ? 1.0f : -1.0f;
+    if (bits) {
+        const uint32_t bit = 1u << (k & 31);
+        if (up)
+            atomicOr(&bits[k >> 5], bit);
+        else
+            atomicAnd(&bits[k >> 5], ~bit);
+    }
+}
+
+// Clears the padding bits [d, roundup32(d)) of the last word (d is not a multiple of 32).
+__global__ void brace_clear_pad_kernel(uint32_t* bits, int64_t d)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0)
+        atomicAnd(&bits[d >> 5], (1u << (d & 31)) - 1u);
+}
+
 // ---------------------------------------------------------------------------------------
 // Measurement aids: a plain streaming read and a plain copy of a buffer of known size.
 // They calibrate what the HBM counters report per byte and give the bandwidth a trivially
@@ -1149,6 +1235,89 @@ int brace_vote_packed_chunk(const uint32_t* signs_dev, int64_t n, int64_t d, int
         return fail(BRACE_ERANGE, "chunk %lld outside [0, %lld)", (long long)chunk, (long long)n);
     return brace_vote_packed_chunks(signs_dev, n, d, ld_words, f, chunk, chunk + 1, params, out_dev,
                                     hip_stream);
+}
+
+int brace_consensus_sums(const int16_t* parts_dev, int64_t g, int64_t d, int64_t ld,
+                         const brace_params_t* params, float* out_dev, void* hip_stream)
+{
+    if (!params)
+        return fail(BRACE_EINVAL, "params is NULL");
+    if (params->struct_size != sizeof(brace_params_t))
+        return fail(BRACE_EINVAL, "params->struct_size is %u, expected %zu", params->struct_size,
+                    sizeof(brace_params_t));
+    if (g < 1 || d < 0)
+        return fail(BRACE_EINVAL, "need g >= 1 and d >= 0");
+    if (g > BRACE_MAX_CLIENTS)
+        return fail(BRACE_ERANGE, "g = %lld exceeds BRACE_MAX_CLIENTS", (long long)g);
+    if (!std::isfinite(params->lambda))
+        return fail(BRACE_EINVAL, "lambda must be finite");
+    if (params->rule != 0 || params->sums_dev)
+        return fail(BRACE_EINVAL, "the consensus of partial sums implements rule 0 and produces "
+                                  "no sign-sums");
+    if (ld == 0)
+        ld = d;
+    if (ld < d)
+        return fail(BRACE_EINVAL, "ld = %lld is smaller than d = %lld", (long long)ld, (long long)d);
+    if (d == 0)
+        return BRACE_OK;
+    uint32_t* bits = static_cast<uint32_t*>(params->out_bits_dev);
+    if (!parts_dev || !aligned_to(parts_dev, 2))
+        return fail(BRACE_EINVAL, "parts_dev must be non-NULL and 2-byte aligned");
+    if (!out_dev && !bits)
+        return fail(BRACE_EINVAL, "no output: out_dev and out_bits_dev are both NULL");
+    if ((out_dev && !aligned_to(out_dev, 4)) || (bits && !aligned_to(bits, 4)))
+        return fail(BRACE_EINVAL, "out_dev and out_bits_dev must be 4-byte aligned");
+    {
+        const char* in_lo = reinterpret_cast<const char*>(parts_dev);
+        const char* in_hi = in_lo + ((g - 1) * ld + d) * 2;
+        const char* o_lo = reinterpret_cast<const char*>(out_dev);
+        if (out_dev && o_lo < in_hi && in_lo < o_lo + d * 4)
+            return fail(BRACE_EINVAL, "out_dev overlaps parts_dev");
+    }
+    int rc = check_device_range(parts_dev, ((g - 1) * ld + d) * 2, "parts_dev");
+    if (rc == BRACE_OK)
+        rc = check_device_range(out_dev, d * 4, "out_dev");
+    if (rc == BRACE_OK)
+        rc = check_device_range(bits, ((d + 31) / 32) * 4, "out_bits_dev");
+    if (rc != BRACE_OK)
+        return rc;
+
+    // |S| <= g * 32767 < 2^30, so thresholds beyond that range saturate.
+    const double fl = std::floor((double)params->lambda);
+    const double lim = 1073741824.0;
+    const int thresh = fl >= lim ? (int)lim + 1 : fl < -lim - 1.0 ? -(int)lim : (int)fl + 1;
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const bool wide = aligned_to(parts_dev, 16) && (ld % 8 == 0 || g == 1) &&
+                      (!out_dev || aligned_to(out_dev, 16));
+    const int64_t octets = wide ? d / 8 : 0;
+    if (octets > 0) {
+        const int64_t grid = (octets + kBlock - 1) / kBlock;
+        if (grid > 0x7fffffffLL)
+            return fail(BRACE_ERANGE, "vector too long for one launch");
+        hipLaunchKernelGGL(brace_consensus_kernel, dim3((unsigned)grid), dim3(kBlock), 0, stream,
+                           parts_dev, ld, (int)g, octets, thresh, out_dev,
+                           reinterpret_cast<uint8_t*>(bits));
+        rc = check_launch("consensus kernel");
+        if (rc != BRACE_OK)
+            return rc;
+    }
+    const int64_t lo = octets * 8;
+    if (lo < d) {
+        const int64_t tgrid = (d - lo + kBlock - 1) / kBlock;
+        if (tgrid > 0x7fffffffLL)
+            return fail(BRACE_ERANGE, "vector too long for one launch");
+        hipLaunchKernelGGL(brace_consensus_tail_kernel, dim3((unsigned)tgrid), dim3(kBlock), 0, stream,
+                           parts_dev, ld, (int)g, lo, d, thresh, out_dev, bits);
+        rc = check_launch("consensus tail kernel");
+        if (rc != BRACE_OK)
+            return rc;
+    }
+    if (bits && (d & 31)) {
+        hipLaunchKernelGGL(brace_clear_pad_kernel, dim3(1), dim3(64), 0, stream, bits, d);
+        rc = check_launch("pad kernel");
+    }
+    return rc;
 }
 
 int brace_rar_aggregate(const float* updates_dev, int64_t n, int64_t d,

@@ -224,6 +224,29 @@ def test_packed_entry_points_validate(L):
     assert L.brace_vote_packed_chunk(None, 8, 3, 0, 1, 5, pr, None, None) == B.BRACE_OK        # empty chunk (d < n)
 
 
+def test_consensus_sums_validates(L):
+    E, R = B.BRACE_EINVAL, B.BRACE_ERANGE
+    p = B.make_params(5.0)
+    pr = ctypes.byref(p)
+    assert L.brace_consensus_sums(FAKE_IN, 4, 100, 0, None, FAKE_OUT, None) == E
+    assert L.brace_consensus_sums(None, 4, 100, 0, pr, FAKE_OUT, None) == E
+    assert L.brace_consensus_sums(FAKE_IN, 0, 100, 0, pr, FAKE_OUT, None) == E
+    assert L.brace_consensus_sums(FAKE_IN, 4, -1, 0, pr, FAKE_OUT, None) == E
+    assert L.brace_consensus_sums(FAKE_IN, 4, 100, 50, pr, FAKE_OUT, None) == E          # ld < d
+    assert L.brace_consensus_sums(FAKE_IN, 4, 100, 0, pr, None, None) == E              # no output
+    assert L.brace_consensus_sums(FAKE_IN + 1, 4, 100, 0, pr, FAKE_OUT, None) == E      # odd address
+    assert L.brace_consensus_sums(FAKE_IN, 4, 100, 0, pr, FAKE_OUT + 2, None) == E
+    assert L.brace_consensus_sums(FAKE_IN, 4, 100, 0, pr, FAKE_IN + 16, None) == E      # overlap
+    assert L.brace_consensus_sums(FAKE_IN, B.BRACE_MAX_CLIENTS + 1, 100, 0, pr, FAKE_OUT, None) == R
+    bad = B.make_params(float("nan"))
+    assert L.brace_consensus_sums(FAKE_IN, 4, 100, 0, ctypes.byref(bad), FAKE_OUT, None) == E
+    maj = B.make_params(0.0, rule=1)
+    assert L.brace_consensus_sums(FAKE_IN, 4, 100, 0, ctypes.byref(maj), FAKE_OUT, None) == E
+    with_sums = B.make_params(5.0, sums_ptr=FAKE_OUT)
+    assert L.brace_consensus_sums(FAKE_IN, 4, 100, 0, ctypes.byref(with_sums), FAKE_OUT, None) == E
+    assert L.brace_consensus_sums(None, 4, 0, 0, pr, None, None) == B.BRACE_OK
+
+
 def test_rar_aggregate_rejects_invalid_arguments(L):
     def call(inp=FAKE_IN, n=4, d=100, mean=0, ld=0, out=FAKE_OUT, size=None, chunk=None):
         p = B.BraceRarParams(ctypes.sizeof(B.BraceRarParams) if size is None else size, mean, ld)
