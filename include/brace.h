@@ -214,6 +214,14 @@ int brace_rar_aggregate_chunk(const float* updates_dev, int64_t n, int64_t d, in
  */
 int brace_set_pointer_checks(int32_t enabled);
 
+/*
+ * Optional: does, for the current device, the host-side set-up that the first call of some
+ * entry points would otherwise do (a device query; opting the burst-writing kernels in to
+ * 128 KiB of LDS).  Callers that capture calls into a HIP graph call it once per device
+ * before the capture, so that the captured calls only launch kernels.  Launches nothing.
+ */
+int brace_init_device(void);
+
 /* Text of the last error on the calling thread ("" if none).  Static storage; do not free. */
 const char* brace_last_error(void);
 

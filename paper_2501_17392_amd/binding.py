@@ -68,7 +68,7 @@ EXPORTS = (
     "brace_aggregate_update", "brace_aggregate_update_chunk", "brace_expand_bits", "brace_apply_bits",
     "brace_packed_row_words", "brace_quantize", "brace_vote_packed", "brace_vote_packed_chunk",
     "brace_vote_packed_chunks", "brace_aggregate_chunks", "brace_consensus_sums",
-    "brace_set_pointer_checks",
+    "brace_set_pointer_checks", "brace_init_device",
 )
 
 
@@ -134,6 +134,8 @@ def lib():
     L.brace_consensus_sums.restype = ctypes.c_int
     L.brace_set_pointer_checks.argtypes = [ctypes.c_int32]
     L.brace_set_pointer_checks.restype = ctypes.c_int
+    L.brace_init_device.argtypes = []
+    L.brace_init_device.restype = ctypes.c_int
     rp = ctypes.POINTER(BraceRarParams)
     L.brace_rar_aggregate.argtypes = [vp, i64, i64, rp, vp, vp]
     L.brace_rar_aggregate.restype = ctypes.c_int
@@ -362,6 +364,11 @@ def brace_aggregate_chunks(updates, f: int, chunk_begin: int, chunk_end: int, la
     _check(lib().brace_aggregate_chunks(updates.data_ptr(), n, d, f, chunk_begin, chunk_end,
                                         ctypes.byref(p), _ptr(out), _stream_handle(stream)))
     return out
+
+
+def brace_init_device():
+    """Host-side set-up for the current device (call once before capturing calls in a HIP graph)."""
+    _check(lib().brace_init_device())
 
 
 def brace_set_pointer_checks(enabled: bool):

@@ -1381,6 +1381,40 @@ int brace_get_tuning(brace_tuning_t* tuning)
     return BRACE_OK;
 }
 
+int brace_init_device(void)
+{
+    // Everything a first call would do on the host besides launching: the device query, the
+    // loading of each translation unit's code object (triggered by asking for a kernel's
+    // attributes) and the LDS opt-in of every burst-writing kernel.
+    (void)compute_units();
+    const void* one_per_unit[] = {
+        reinterpret_cast<const void*>(brace_vote_pick_v1(1, 2, 1, 0, 0)),
+        reinterpret_cast<const void*>(brace_vote_pick_v2(1, 2, 1, 0, 0)),
+        reinterpret_cast<const void*>(brace_vote_pick_v4(1, 2, 1, 0, 0)),
+        reinterpret_cast<const void*>(brace_sum_pick_v1(1, 2, 1, 0, 0)),
+        reinterpret_cast<const void*>(brace_sum_pick_v2(1, 2, 1, 0, 0)),
+        reinterpret_cast<const void*>(brace_sum_pick_v4(1, 2, 1, 0, 0)),
+        reinterpret_cast<const void*>(brace_expand_kernel),
+    };
+    for (const void* k : one_per_unit) {
+        hipFuncAttributes fa;
+        const hipError_t err = hipFuncGetAttributes(&fa, k);
+        if (err != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(BRACE_EHIP, "cannot load a kernel: %s", hipGetErrorString(err));
+        }
+    }
+    for (int v = 2; v <= 4; v += 2)
+        for (int pipe = 0; pipe <= 1; ++pipe) {
+            int rc = allow_stage_lds(reinterpret_cast<const void*>(brace_vote_pick_staged(v, pipe)));
+            if (rc == BRACE_OK)
+                rc = allow_stage_lds(reinterpret_cast<const void*>(brace_sum_pick_staged(v, pipe)));
+            if (rc != BRACE_OK)
+                return rc;
+        }
+    return allow_stage_lds(reinterpret_cast<const void*>(brace_quantize_staged_kernel));
+}
+
 int brace_set_pointer_checks(int32_t enabled)
 {
     g_pointer_checks = enabled != 0;

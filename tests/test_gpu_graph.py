@@ -73,3 +73,59 @@ def test_chunk_loop_and_whole_call_in_a_graph():
         B.brace_aggregate(upd, f, lam, out=eager)
         torch.cuda.synchronize()
         assert torch.equal(eager, out_whole)
+
+
+def test_planes_route_in_a_graph_after_init_device():
+    """Quantise once, vote per run of chunks on the planes, Phase III on partial sums, burst-writing
+    sum: captured with only brace_init_device() before (no warm-up launches), replayed and checked
+    against the oracle each time.  Rows are long enough for the burst kernels (128 spans, >= 8
+    rounds of blocks is forced through the tuning)."""
+    assert torch.cuda.is_available()
+    B.lib()
+    B.brace_reset_tuning()
+    n, d, lam = 6, 128 * 4096 * 2 + 4097, 1.0
+    upd = torch.empty(n, d, device=DEV)
+    fill(upd, 1)
+    signs = torch.zeros(n, B.brace_packed_row_words(d), device=DEV, dtype=torch.int32)
+    out = torch.zeros(d, device=DEV)
+    bits = torch.zeros((d + 31) // 32, device=DEV, dtype=torch.int32)
+    parts = torch.zeros(2, d, device=DEV, dtype=torch.int16)
+    out3 = torch.zeros(d, device=DEV)
+    total = torch.zeros(d, device=DEV)
+
+    B.brace_init_device()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    try:
+        B.brace_set_tuning(stage_writes=2)
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                B.brace_quantize(upd, signs)
+                bits.zero_()                      # a fill kernel, not a memset node
+                B.brace_vote_packed_chunks(signs, d, 0, 0, 2, lam, out=out, out_bits=bits)
+                B.brace_vote_packed_chunks(signs, d, 0, 2, n, lam, out=out, out_bits=bits)
+                B.brace_aggregate(upd[:3], 0, 0.0, sums=parts[0])
+                B.brace_aggregate(upd[3:], 0, 0.0, sums=parts[1])
+                B.brace_consensus_sums(parts, lam, out=out3)
+                B.brace_rar_aggregate(upd, total)
+    finally:
+        B.brace_reset_tuning()
+    torch.cuda.synchronize()
+
+    for replay in range(3):
+        fill(upd, 200 + replay)
+        out.fill_(7.0)
+        out3.fill_(7.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        host = upd.cpu().numpy()
+        want = O.brace_direct(host, lam)
+        assert np.array_equal(signs.cpu().numpy().view(np.uint32), O.sign_planes(host)), replay
+        assert np.array_equal(out.cpu().numpy(), want.out), replay
+        assert np.array_equal(out3.cpu().numpy(), want.out), replay
+        assert np.array_equal(bits.cpu().numpy().view(np.uint8)[: (d + 7) // 8], want.bits), replay
+        ref = O.rar_sum_direct(host)
+        got = total.cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(got - ref) <= 1e-6 + 1e-5 * np.abs(ref)), replay
