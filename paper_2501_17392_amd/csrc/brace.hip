@@ -19,9 +19,16 @@ namespace {
 
 using namespace brace_dev;
 
-// Ranges with fewer 1024-coordinate groups than this are written in one kernel: the second
-// launch would cost more than separating the writes from the read stream saves.
-constexpr int64_t kSplitMinGroups = 2048;
+// Writing the floats from a second kernel pays once the matrix range is well past the
+// 256 MiB memory-side cache: below that, stores from inside the read stream cost nothing
+// measurable and the second launch is pure overhead (n = 8, d = 8 M, 256 MB: 52 us in one
+// kernel, 58 us split; n = 32, d = 4 M, 512 MB: 85 against 87 us); above it the split wins
+// (n = 100, d = 2 M, 800 MB: 119 against 122 us; n = 100, d = 25 M: 1.44 against 1.51 ms).
+constexpr int64_t kSplitMinBytes = (int64_t)512 << 20;
+// With few clients the floats are a large share of the traffic and the second kernel has
+// to write all of them on its own; LDS-staged bursts from the first kernel are cheaper
+// (n = 8, d = 100 M: 582 us staged, 618 us split; equal at n = 16, split ahead from n = 24).
+constexpr int64_t kStageBelowClients = 16;
 
 thread_local char g_err[256] = "";
 
@@ -635,9 +642,19 @@ int launch_vote(const float* updates, int64_t n, int64_t d, int64_t ld, int thre
     bool split = (out || w) && (!out || aligned_to(out, 16)) && (!w || (bits && aligned_to(w, 16))) &&
                  groups > 0 && t.split_writes != 1;
     if (split && t.split_writes != 2)
-        split = groups >= kSplitMinGroups;
+        split = 4 * n * (hi - lo) >= kSplitMinBytes;
     if (p->rule == 1)
         split = false;             // three values do not fit the bit-words
+    if (split && t.split_writes == 0 && t.stage_writes == 0 && n < kStageBelowClients && !bits &&
+        !p->sums_dev) {
+        // Few clients: prefer bursts from this kernel if the range qualifies for them.
+        StreamArgs a0;
+        Shape sh0;
+        (void)plan_range(a0, sh0, t, n, ld, v, 64 * (int64_t)v, lo, hi, hi);
+        const int64_t slots0 = (a0.hi_a - a0.lo_a) / (64 * (int64_t)v);
+        if (stage_tiles_for(t, sh0, v, slots0, out, w) > 0)
+            split = false;
+    }
 
     VoteOp op;
     op.out = out;
