@@ -546,10 +546,14 @@ int check_buffers(const float* updates, int64_t n, int64_t d, int64_t ld, const 
 // Staged (burst-write) launch: legal when the op writes one float per coordinate to 16-byte
 // aligned arrays with 2- or 4-dword accesses; chosen for ranges large enough to get the
 // widest tile anyway.  Returns the tiles per block (0 = use the ordinary kernel).
-int stage_tiles_for(const brace_tuning_t& t, const Shape& sh, int v, int64_t slots,
+int stage_tiles_for(const brace_tuning_t& t, const Shape& sh, int v, int64_t slots, int64_t n,
                     const void* out, const void* w)
 {
     if (t.stage_writes == 1 || (v != 2 && v != 4) || sh.rowsplit)
+        return 0;
+    // A range that fits the memory-side cache gains nothing from bursts (n = 8, d = 8 M:
+    // 44.6 us with stores per wave, 47.8 us staged).
+    if (t.stage_writes != 2 && 4 * n * slots * 64 * v < kSplitMinBytes)
         return 0;
     if ((out && !aligned_to(out, 16)) || (w && !aligned_to(w, 16)))
         return 0;
@@ -652,7 +656,7 @@ int launch_vote(const float* updates, int64_t n, int64_t d, int64_t ld, int thre
         Shape sh0;
         (void)plan_range(a0, sh0, t, n, ld, v, 64 * (int64_t)v, lo, hi, hi);
         const int64_t slots0 = (a0.hi_a - a0.lo_a) / (64 * (int64_t)v);
-        if (stage_tiles_for(t, sh0, v, slots0, out, w) > 0)
+        if (stage_tiles_for(t, sh0, v, slots0, n, out, w) > 0)
             split = false;
     }
 
@@ -682,7 +686,7 @@ int launch_vote(const float* updates, int64_t n, int64_t d, int64_t ld, int thre
 
     const int64_t slots = (a.hi_a - a.lo_a) / (64 * (int64_t)v);
     const bool plain_floats = !split && !bits && !p->sums_dev && (out || w);
-    const int stage = plain_floats ? stage_tiles_for(t, sh, v, slots, out, w) : 0;
+    const int stage = plain_floats ? stage_tiles_for(t, sh, v, slots, n, out, w) : 0;
     if (stage > 0) {
         const int64_t per_block = (int64_t)stage * kWaves * kStageCols;
         const int64_t sgrid = (slots + per_block - 1) / per_block + a.edge_blocks;
@@ -748,7 +752,7 @@ int launch_sum(const float* updates, int64_t n, int64_t d, int64_t ld, double sc
         return fail(BRACE_ERANGE, "range needs %lld blocks, more than one launch can hold",
                     (long long)grid);
     const int64_t slots = (a.hi_a - a.lo_a) / (64 * (int64_t)v);
-    const int stage = stage_tiles_for(t, sh, v, slots, out, nullptr);
+    const int stage = stage_tiles_for(t, sh, v, slots, n, out, nullptr);
     if (stage > 0) {
         const int64_t per_block = (int64_t)stage * kWaves * kStageCols;
         const int64_t sgrid = (slots + per_block - 1) / per_block + a.edge_blocks;
@@ -1060,12 +1064,17 @@ int brace_quantize(const float* updates_dev, int64_t n, int64_t d, int64_t ld,
     const int64_t groups = (spans + kQuantGroup - 1) / kQuantGroup;    // per row
     const brace_tuning_t t = g_tuning;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    // Bursts pay when the blocks (one per compute unit at a time, 2 MiB of input each) come in
-    // many rounds; with few rounds the part-filled last one costs more than the bursts save
-    // (n = 50, d = 11 M: 4.3 rounds, 0.447 ms against 0.408 ms with a store per span).
+    // The burst kernel runs one block per compute unit at a time (2 MiB of input each), so its
+    // blocks come in rounds and a thinly filled last round costs as much as a full one.
+    // Measured: ahead by 2-5 % with well filled rounds (n = 64, d = 8 M: 4.0 rounds; n = 8,
+    // d = 100 M: 5.97; n = 100, d = 25 M: 18.75), behind with ragged ones (n = 50, d = 11 M:
+    // 4.3 rounds, 0.447 against 0.408 ms; n = 100, d = 8 M: 6.25 rounds, 601 against 572 us).
     const int64_t cus = compute_units() > 0 ? compute_units() : 256;
+    const int64_t blocks = groups * n;
+    const double fill = (double)blocks / (double)((blocks + cus - 1) / cus * cus);
     const bool staged = t.stage_writes == 2 ||
-                        (t.stage_writes == 0 && spans >= kQuantGroup && groups * n >= 8 * cus);
+                        (t.stage_writes == 0 && spans >= kQuantGroup && blocks >= 4 * cus &&
+                         fill >= 0.9);
     if (staged) {
         const int64_t grid = groups * n;
         if (grid > 0x7fffffffLL)
