@@ -29,6 +29,7 @@ constexpr int64_t kSplitMinBytes = (int64_t)512 << 20;
 // to write all of them on its own; LDS-staged bursts from the first kernel are cheaper
 // (n = 8, d = 100 M: 582 us staged, 618 us split; equal at n = 16, split ahead from n = 24).
 constexpr int64_t kStageBelowClients = 16;
+constexpr int64_t kNarrowBelowClients = 48;
 
 thread_local char g_err[256] = "";
 
@@ -444,7 +445,10 @@ Shape choose_shape(const brace_tuning_t& t, int64_t slots, int64_t n)
     Shape s;
     s.cols = t.cols;
     if (s.cols == 0) {
-        s.cols = 8;
+        // With few client rows a wave is short-lived and its start-up and epilogue weigh more
+        // than long contiguous runs gain: 4 loads per row below 48 clients (n = 4: 239 us
+        // against 384 us with 8; n = 8: 488 / 537; n = 32: 561 / 572; n = 64: 3.76 / 3.75 ms).
+        s.cols = n < kNarrowBelowClients ? 4 : 8;
         while (s.cols > 1 && slots / s.cols < target)
             s.cols >>= 1;
     }
@@ -456,7 +460,7 @@ Shape choose_shape(const brace_tuning_t& t, int64_t slots, int64_t n)
         s.cols = kRowsplitMaxCols;
     s.unroll = t.unroll;
     if (s.unroll == 0) {
-        s.unroll = s.cols >= 8 ? 2 : 4;
+        s.unroll = s.cols >= 4 ? 2 : 4;             // 4 loads x 4 rows double-buffered runs out of registers
         const int64_t rows = s.rowsplit ? n / kWaves : n;
         while (s.unroll > 2 && 2 * s.unroll > rows)
             s.unroll >>= 1;
@@ -557,15 +561,20 @@ int stage_tiles_for(const brace_tuning_t& t, const Shape& sh, int v, int64_t slo
         return 0;
     if ((out && !aligned_to(out, 16)) || (w && !aligned_to(w, 16)))
         return 0;
-    if (t.stage_writes != 2 && (t.cols != 0 || t.unroll != 0 || sh.cols != kStageCols))
+    // The large-range shapes: 8 loads per row, or 4 where that is the choice for few clients
+    // (and not a tile shrunk because the range is short).
+    const bool stage_shape = sh.cols == kStageColsWide ||
+                             (sh.cols == kStageColsNarrow && n < kNarrowBelowClients);
+    if (t.stage_writes != 2 && (t.cols != 0 || t.unroll != 0 || !stage_shape))
         return 0;                  // explicit tile tuning, or a short range: ordinary kernel
+    const int scols = sh.cols == kStageColsNarrow ? kStageColsNarrow : kStageColsWide;
     // The LDS burst limits a compute unit to one block, so the blocks run in rounds of one
     // per unit and a last, part-filled round costs as much as a full one.  Among the burst
     // sizes that fit, take the largest whose rounds are (nearly) as full as the best one.
-    const size_t tile_bytes = (size_t)kWaves * kStageCols * 64 * v * 4;
+    const size_t tile_bytes = (size_t)kWaves * scols * 64 * v * 4;
     const int max_tiles = (int)(kStageBytes / tile_bytes);
     const int64_t cus = compute_units() > 0 ? compute_units() : 256;
-    const int64_t tiles = (slots + kWaves * kStageCols - 1) / (kWaves * kStageCols);
+    const int64_t tiles = (slots + kWaves * scols - 1) / (kWaves * scols);
     int best = 0;
     double best_fill = 0.0;
     for (int k = 2; k <= max_tiles; ++k) {
@@ -686,11 +695,16 @@ int launch_vote(const float* updates, int64_t n, int64_t d, int64_t ld, int thre
 
     const int64_t slots = (a.hi_a - a.lo_a) / (64 * (int64_t)v);
     const bool plain_floats = !split && !bits && !p->sums_dev && (out || w);
-    const int stage = plain_floats ? stage_tiles_for(t, sh, v, slots, n, out, w) : 0;
+    // The in-place update moves 8 bytes per coordinate; below 16 clients that is so large a
+    // share of the traffic that the burst's read-modify-write stalls more than it saves
+    // (n = 8, d = 100 M: 666 us with stores per wave, 727 us staged; n = 16: 604 / 591).
+    const bool stage_ok = plain_floats && (!w || n >= kStageBelowClients || t.stage_writes == 2);
+    const int stage = stage_ok ? stage_tiles_for(t, sh, v, slots, n, out, w) : 0;
     if (stage > 0) {
-        const int64_t per_block = (int64_t)stage * kWaves * kStageCols;
+        const int scols = sh.cols == kStageColsNarrow ? kStageColsNarrow : kStageColsWide;
+        const int64_t per_block = (int64_t)stage * kWaves * scols;
         const int64_t sgrid = (slots + per_block - 1) / per_block + a.edge_blocks;
-        stream_staged_kernel_t<VoteOp> ks = brace_vote_pick_staged(v, t.pipeline);
+        stream_staged_kernel_t<VoteOp> ks = brace_vote_pick_staged(v, scols, t.pipeline);
         rc = allow_stage_lds(reinterpret_cast<const void*>(ks));
         if (rc != BRACE_OK)
             return rc;
@@ -754,9 +768,10 @@ int launch_sum(const float* updates, int64_t n, int64_t d, int64_t ld, double sc
     const int64_t slots = (a.hi_a - a.lo_a) / (64 * (int64_t)v);
     const int stage = stage_tiles_for(t, sh, v, slots, n, out, nullptr);
     if (stage > 0) {
-        const int64_t per_block = (int64_t)stage * kWaves * kStageCols;
+        const int scols = sh.cols == kStageColsNarrow ? kStageColsNarrow : kStageColsWide;
+        const int64_t per_block = (int64_t)stage * kWaves * scols;
         const int64_t sgrid = (slots + per_block - 1) / per_block + a.edge_blocks;
-        stream_staged_kernel_t<SumOp> ks = brace_sum_pick_staged(v, t.pipeline);
+        stream_staged_kernel_t<SumOp> ks = brace_sum_pick_staged(v, scols, t.pipeline);
         const int rcs = allow_stage_lds(reinterpret_cast<const void*>(ks));
         if (rcs != BRACE_OK)
             return rcs;
@@ -1431,13 +1446,16 @@ int brace_init_device(void)
         }
     }
     for (int v = 2; v <= 4; v += 2)
-        for (int pipe = 0; pipe <= 1; ++pipe) {
-            int rc = allow_stage_lds(reinterpret_cast<const void*>(brace_vote_pick_staged(v, pipe)));
-            if (rc == BRACE_OK)
-                rc = allow_stage_lds(reinterpret_cast<const void*>(brace_sum_pick_staged(v, pipe)));
-            if (rc != BRACE_OK)
-                return rc;
-        }
+        for (int cols = kStageColsNarrow; cols <= kStageColsWide; cols += kStageColsWide - kStageColsNarrow)
+            for (int pipe = 0; pipe <= 1; ++pipe) {
+                int rc = allow_stage_lds(
+                    reinterpret_cast<const void*>(brace_vote_pick_staged(v, cols, pipe)));
+                if (rc == BRACE_OK)
+                    rc = allow_stage_lds(
+                        reinterpret_cast<const void*>(brace_sum_pick_staged(v, cols, pipe)));
+                if (rc != BRACE_OK)
+                    return rc;
+            }
     return allow_stage_lds(reinterpret_cast<const void*>(brace_quantize_staged_kernel));
 }
 

@@ -357,15 +357,19 @@ stream_staged_kernel(const float* __restrict__ updates, const StreamArgs a, cons
 template <class Op>
 using stream_staged_kernel_t = void (*)(const float*, const StreamArgs, const Op, int);
 
-constexpr int kStageCols = 8;               // the staged variant exists for the large-range shape
+constexpr int kStageColsWide = 8;           // the staged variant exists for the two large-range
+constexpr int kStageColsNarrow = 4;         // shapes: 8 loads per row, and 4 for few clients
 constexpr int kStageUnroll = 2;
 constexpr size_t kStageBytes = 128 * 1024;  // burst per block; the LDS of a compute unit is 160 KiB
 
 template <class Op, int V>
-stream_staged_kernel_t<Op> pick_staged(int pipe)
+stream_staged_kernel_t<Op> pick_staged(int cols, int pipe)
 {
-    return pipe ? stream_staged_kernel<Op, V, kStageCols, kStageUnroll, true>
-                : stream_staged_kernel<Op, V, kStageCols, kStageUnroll, false>;
+    if (cols == kStageColsNarrow)
+        return pipe ? stream_staged_kernel<Op, V, kStageColsNarrow, kStageUnroll, true>
+                    : stream_staged_kernel<Op, V, kStageColsNarrow, kStageUnroll, false>;
+    return pipe ? stream_staged_kernel<Op, V, kStageColsWide, kStageUnroll, true>
+                : stream_staged_kernel<Op, V, kStageColsWide, kStageUnroll, false>;
 }
 
 // Kernel lookup by launch tuning; instantiates the whole table for one (Op, V).  Row-split
