@@ -551,9 +551,11 @@ int check_buffers(const float* updates, int64_t n, int64_t d, int64_t ld, const 
 // aligned arrays with 2- or 4-dword accesses; chosen for ranges large enough to get the
 // widest tile anyway.  Returns the tiles per block (0 = use the ordinary kernel).
 int stage_tiles_for(const brace_tuning_t& t, const Shape& sh, int v, int64_t slots, int64_t n,
-                    const void* out, const void* w)
+                    const void* out, const void* w, const void* sums = nullptr)
 {
     if (t.stage_writes == 1 || (v != 2 && v != 4) || sh.rowsplit)
+        return 0;
+    if (sums && !aligned_to(sums, 8))
         return 0;
     // A range that fits the memory-side cache gains nothing from bursts (n = 8, d = 8 M:
     // 44.6 us with stores per wave, 47.8 us staged).
@@ -679,6 +681,7 @@ int launch_vote(const float* updates, int64_t n, int64_t d, int64_t ld, int thre
     op.zero_sign = p->zero_sign;
     op.split = split ? 1 : 0;
     op.tie_zero = p->rule == 1 ? 1 : 0;
+    op.stage_sums = 0;
 
     int64_t hi_ext = hi;
     if (bits && hi == d)
@@ -699,7 +702,15 @@ int launch_vote(const float* updates, int64_t n, int64_t d, int64_t ld, int thre
     // share of the traffic that the burst's read-modify-write stalls more than it saves
     // (n = 8, d = 100 M: 666 us with stores per wave, 727 us staged; n = 16: 604 / 591).
     const bool stage_ok = plain_floats && (!w || n >= kStageBelowClients || t.stage_writes == 2);
-    const int stage = stage_ok ? stage_tiles_for(t, sh, v, slots, n, out, w) : 0;
+    // Sign-sums alone (the partial sums a device contributes to Share-Reduce) are staged the
+    // same way (n = 12, d = 100 M: 852 us with stores per wave, 727 us for the reads alone).
+    const bool sums_only = p->sums_dev && !out && !w && !bits;
+    int stage = 0;
+    if (stage_ok)
+        stage = stage_tiles_for(t, sh, v, slots, n, out, w);
+    else if (sums_only)
+        stage = stage_tiles_for(t, sh, v, slots, n, nullptr, nullptr, p->sums_dev);
+    op.stage_sums = (stage > 0 && sums_only) ? 1 : 0;
     if (stage > 0) {
         const int scols = sh.cols == kStageColsNarrow ? kStageColsNarrow : kStageColsWide;
         const int64_t per_block = (int64_t)stage * kWaves * scols;

@@ -32,6 +32,7 @@ struct VoteOp {
     int32_t zero_sign;      // vote of +-0 and NaN
     int32_t split;          // 1: the body emits bit-words only (a second kernel writes the floats)
     int32_t tie_zero;       // 1: majority rule, S == 0 gives 0 (thresh is 1 then)
+    int32_t stage_sums;     // 1: the staged kernel delivers the sign-sums (and nothing else)
 
     // Two counters per coordinate: clients voting +1 and clients voting -1.
     struct State { int pos, neg; };
@@ -141,14 +142,24 @@ struct VoteOp {
             atomicAnd(&bits[k >> 5], ~(1u << (k & 31)));
     }
 
-    // Staged variant (float result and / or in-place model update only; no bits, no sums).
+    // Staged variant: the float result and / or the in-place model update, or (stage_sums)
+    // the sign-sums alone -- the partial sums of Share-Reduce, exact in a float up to 2^24.
     __device__ __forceinline__ float stage_value(const State& st, int n) const
     {
-        return decide(sign_sum(st, n));
+        const int s = sign_sum(st, n);
+        return stage_sums ? (float)s : decide(s);
     }
 
     __device__ __forceinline__ void flush4(int64_t k, f32x4 v) const
     {
+        if (stage_sums) {
+            typename IVec<4>::type s4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                s4[e] = (short)v[e];
+            __builtin_nontemporal_store(s4, reinterpret_cast<typename IVec<4>::type*>(sums + k));
+            return;
+        }
         if (out)
             __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(out + k));
         if (w) {

@@ -96,3 +96,35 @@ def test_phases_chained_on_the_gpu_equal_the_one_pass_vote(n, groups, d):
             torch.cuda.synchronize()
             assert np.array_equal(out.cpu().numpy(), want.out), (n, groups, d, zs, lam)
             assert np.array_equal(bits.cpu().numpy().view(np.uint8)[: (d + 7) // 8], want.bits)
+
+
+@pytest.mark.parametrize("n,d,ld,offset,soff", [
+    (1, 1, None, 0, 0), (3, 1024, None, 0, 0), (5, 8192 * 3 + 5, None, 0, 0), (12, 100_003, None, 0, 0),
+    (12, 100_003, 100_004, 0, 0), (12, 100_002, None, 0, 0), (7, 70_001, None, 1, 0),
+    (9, 50_000, None, 0, 1), (9, 50_000, None, 0, 2), (9, 50_000, None, 0, 4), (40, 300_007, None, 0, 0)])
+@pytest.mark.parametrize("stage", [0, 1, 2], ids=["auto", "per-wave-stores", "bursts"])
+def test_sign_sums_alone_match_the_oracle(n, d, ld, offset, soff, stage):
+    """Phase I + II delivered as data (what a device contributes to Share-Reduce): the int16
+    sign-sums as the only output, with per-wave stores and with LDS-staged bursts."""
+    rng = np.random.default_rng(n * 17 + d + soff)
+    g = rng.standard_normal((n, d)).astype(np.float32)
+    g[rng.random((n, d)) < 0.1] = 0.0
+    g[rng.random((n, d)) < 0.03] = -0.0
+    g[rng.random((n, d)) < 0.02] = np.nan
+    ld = d if ld is None else ld
+    store = torch.full((n * ld + offset + 8,), float("nan"), device=DEV, dtype=torch.float32)
+    upd = store[offset: offset + n * ld].view(n, ld)[:, :d]
+    upd.copy_(torch.from_numpy(g))
+    for zs in (0, 1, -1):
+        whole = torch.full((d + 128 + soff,), 12345, device=DEV, dtype=torch.int16)
+        sums = whole[64 + soff: 64 + soff + d]
+        try:
+            B.brace_set_tuning(stage_writes=stage)
+            B.brace_aggregate(upd, 0, 0.0, zs, sums=sums)
+        finally:
+            B.brace_reset_tuning()
+        torch.cuda.synchronize()
+        h = whole.cpu().numpy()
+        want = O.sign_quantize(g, zs).sum(axis=0)
+        assert np.array_equal(h[64 + soff: 64 + soff + d].astype(np.int64), want), (n, d, zs, stage)
+        assert (h[: 64 + soff] == 12345).all() and (h[64 + soff + d:] == 12345).all()
