@@ -29,6 +29,11 @@ test, none is pinned by a printed value):
   coordinate than the rest.                              [parity unpinned]
 * packed output: bit j of byte b is coordinate 8*b + j, 1 means +1.
                                                          [parity unpinned]
+* bit planes of the quantise-once form (sign_planes): per client, word pair j
+  = ("x > 0" bits, "x < 0" bits) of coordinates 32j .. 32j+31, LSB first, rows
+  padded to an even number of pairs.  A storage convention of this build, not
+  of the paper; what is computed from the planes is pinned through Eq. (1).
+                                                         [parity unpinned]
 Pinned by the paper: Eq. (1) itself incl. the tie sum == lambda -> -1, the
 ring direction and chunk ownership (three-client example of Sec. 2.2), the
 attacked sum [22, 1, -185] (Sec. 3), the traffic closed forms (Table 1) and
