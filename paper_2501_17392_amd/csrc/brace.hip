@@ -342,6 +342,18 @@ bool aligned_to(const void* p, uintptr_t bytes)
     return (reinterpret_cast<uintptr_t>(p) & (bytes - 1)) == 0;
 }
 
+// Sizes are caller-supplied 64-bit numbers: a matrix of `rows` rows with pitch `pitch` must
+// stay far inside the address space (2^47 bytes), so that no byte count computed from it
+// can overflow.  Returns BRACE_OK or fails with BRACE_ERANGE.
+int check_extent(int64_t rows, int64_t pitch, int64_t elem_bytes)
+{
+    const int64_t limit = ((int64_t)1 << 47) / elem_bytes;
+    if (pitch > limit || rows > limit / (pitch > 0 ? pitch : 1))
+        return fail(BRACE_ERANGE, "a matrix of %lld rows with pitch %lld does not fit the address space",
+                    (long long)rows, (long long)pitch);
+    return BRACE_OK;
+}
+
 int validate(const float* updates, int64_t n, int64_t d, int64_t f, const brace_params_t* p,
              const float* out, int64_t* ld_out, int* thresh_out)
 {
@@ -371,6 +383,8 @@ int validate(const float* updates, int64_t n, int64_t d, int64_t f, const brace_
                     (long long)d);
     *ld_out = p->ld ? p->ld : d;
     *thresh_out = 0;
+    if (check_extent(n, *ld_out, 4) != BRACE_OK)
+        return BRACE_ERANGE;
     if (d == 0)
         return BRACE_OK;       // nothing is read or written, so empty buffers may be NULL
     if (!updates)
@@ -826,6 +840,8 @@ int validate_rar(const float* updates, int64_t n, int64_t d, const brace_rar_par
     const int64_t ld = p->ld ? p->ld : d;
     *ld_out = ld;
     *scale_out = p->mean ? 1.0 / (double)n : 1.0;
+    if (check_extent(n, ld, 4) != BRACE_OK)
+        return BRACE_ERANGE;
     if (d == 0)
         return BRACE_OK;
     if (!updates || !out)
@@ -1025,6 +1041,8 @@ int brace_expand_bits(const void* bits_dev, int64_t d, float* out_dev, void* hip
 {
     if (d < 0)
         return fail(BRACE_EINVAL, "d must be >= 0");
+    if (check_extent(1, d, 4) != BRACE_OK)
+        return BRACE_ERANGE;
     if (d > 0 && (!bits_dev || !out_dev || !aligned_to(bits_dev, 4) || !aligned_to(out_dev, 4)))
         return fail(BRACE_EINVAL, "bits_dev and out_dev must be non-NULL and 4-byte aligned");
     return launch_from_bits(static_cast<const uint32_t*>(bits_dev), d, out_dev, nullptr, 0.0f,
@@ -1035,6 +1053,8 @@ int brace_apply_bits(const void* bits_dev, int64_t d, float eta, float* w_dev, v
 {
     if (d < 0)
         return fail(BRACE_EINVAL, "d must be >= 0");
+    if (check_extent(1, d, 4) != BRACE_OK)
+        return BRACE_ERANGE;
     if (!std::isfinite(eta))
         return fail(BRACE_EINVAL, "eta must be finite");
     if (d > 0 && (!bits_dev || !w_dev || !aligned_to(bits_dev, 4) || !aligned_to(w_dev, 4)))
@@ -1047,7 +1067,7 @@ int64_t brace_packed_row_words(int64_t d)
 {
     if (d < 0)
         return 0;
-    int64_t w = (d + 31) / 32;
+    int64_t w = d / 32 + (d % 32 != 0);        // no overflow for any d
     w += w & 1;
     return 2 * w;
 }
@@ -1065,8 +1085,12 @@ int brace_quantize(const float* updates_dev, int64_t n, int64_t d, int64_t ld,
         ld_words = brace_packed_row_words(d);
     if (ld < d)
         return fail(BRACE_EINVAL, "ld = %lld is smaller than d = %lld", (long long)ld, (long long)d);
+    if (check_extent(n, ld, 4) != BRACE_OK)
+        return BRACE_ERANGE;
     if (ld_words < brace_packed_row_words(d) || (ld_words & 3))
         return fail(BRACE_EINVAL, "ld_words must be a multiple of 4 and >= brace_packed_row_words(d)");
+    if (check_extent(n, ld_words, 4) != BRACE_OK)
+        return BRACE_ERANGE;
     if (d == 0)
         return BRACE_OK;
     if (!updates_dev || !signs_dev || !aligned_to(updates_dev, 4) || !aligned_to(signs_dev, 16))
@@ -1148,8 +1172,12 @@ static int packed_range(const uint32_t* signs_dev, int64_t n, int64_t d, int64_t
         return fail(BRACE_EINVAL, "sign-sums are not produced from packed signs");
     if (ld_words == 0)
         ld_words = brace_packed_row_words(d);
+    if (d > ((int64_t)1 << 45))
+        return fail(BRACE_ERANGE, "d = %lld does not fit the address space", (long long)d);
     if (ld_words < brace_packed_row_words(d) || (ld_words & 3))
         return fail(BRACE_EINVAL, "ld_words must be a multiple of 4 and >= brace_packed_row_words(d)");
+    if (check_extent(n, ld_words, 4) != BRACE_OK)
+        return BRACE_ERANGE;
     if (d == 0 || hi <= lo)
         return BRACE_OK;
     uint32_t* bits = static_cast<uint32_t*>(params->out_bits_dev);
@@ -1310,6 +1338,8 @@ int brace_consensus_sums(const int16_t* parts_dev, int64_t g, int64_t d, int64_t
         ld = d;
     if (ld < d)
         return fail(BRACE_EINVAL, "ld = %lld is smaller than d = %lld", (long long)ld, (long long)d);
+    if (check_extent(g, ld, 4) != BRACE_OK)
+        return BRACE_ERANGE;
     if (d == 0)
         return BRACE_OK;
     uint32_t* bits = static_cast<uint32_t*>(params->out_bits_dev);

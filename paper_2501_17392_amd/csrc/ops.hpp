@@ -103,15 +103,15 @@ struct VoteOp {
         if (bits || split) {
             // 32/V lanes share one 32-bit word; OR them together, the first lane stores.
             constexpr int L = 32 / V;
-            uint32_t w = mybits << (V * (lane & (L - 1)));
+            uint32_t word = mybits << (V * (lane & (L - 1)));
 #pragma unroll
             for (int m = 1; m < L; m <<= 1)
-                w |= (uint32_t)__shfl_xor((int)w, m, 64);
+                word |= (uint32_t)__shfl_xor((int)word, m, 64);
             if ((lane & (L - 1)) == 0) {
                 if (bits)
-                    bits[k >> 5] = w;
+                    bits[k >> 5] = word;
                 else
-                    reinterpret_cast<uint32_t*>(out)[scratch_word(k)] = w;
+                    reinterpret_cast<uint32_t*>(out)[scratch_word(k)] = word;
             }
         }
     }

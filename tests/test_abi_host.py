@@ -59,6 +59,27 @@ def test_header_is_plain_c_and_host_entry_points_work_from_c(L, tmp_path):
     assert "abi_host ok" in res.stdout
 
 
+def test_host_planning_survives_random_arguments(L, tmp_path):
+    """200,000 random calls (sizes up to 2^63, every alignment, every tuning) with the pointer
+    checks off: on a machine without a GPU each call runs all of its host arithmetic and fails
+    at the launch, so the program must end with status codes only.  (The same program linked
+    against a host-sanitised build of the library is the overflow check; see tests/c/abi_fuzz.c.)"""
+    import subprocess
+    import torch
+    if torch.cuda.device_count() > 0:
+        pytest.skip("needs a machine without a GPU: the buffers are made-up addresses")
+    exe = str(tmp_path / "abi_fuzz")
+    src = os.path.join(ROOT, "tests", "c", "abi_fuzz.c")
+    libdir = os.path.dirname(B.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-O1", "-Wall", "-Wextra", "-Werror",
+                    "-I", os.path.join(ROOT, "include"), src, "-o", exe,
+                    "-L", libdir, "-lbrace", "-lm", f"-Wl,-rpath,{libdir}",
+                    "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    res = subprocess.run([exe], capture_output=True, text=True, timeout=300)
+    assert res.returncode == 0, res.stdout + res.stderr
+    assert "abi_fuzz ok" in res.stdout
+
+
 def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(B.BraceParams) == 40
     assert B.BraceParams.ld.offset == 16
@@ -245,6 +266,31 @@ def test_consensus_sums_validates(L):
     with_sums = B.make_params(5.0, sums_ptr=FAKE_OUT)
     assert L.brace_consensus_sums(FAKE_IN, 4, 100, 0, ctypes.byref(with_sums), FAKE_OUT, None) == E
     assert L.brace_consensus_sums(None, 4, 0, 0, pr, None, None) == B.BRACE_OK
+
+
+def test_absurd_sizes_are_range_errors_not_overflows(L):
+    """Caller-supplied 64-bit sizes never reach arithmetic that could overflow."""
+    R = B.BRACE_ERANGE
+    p = B.make_params(5.0)
+    pr = ctypes.byref(p)
+    huge = 1 << 62
+    assert L.brace_aggregate(FAKE_IN, 4, huge, 1, pr, FAKE_OUT, None) == R
+    assert L.brace_aggregate(FAKE_IN, 32767, 1 << 40, 1, pr, FAKE_OUT, None) == R
+    assert L.brace_aggregate_chunk(FAKE_IN, 4, huge, 1, 0, pr, FAKE_OUT, None) == R
+    wide = B.make_params(5.0, ld=huge)
+    assert L.brace_aggregate(FAKE_IN, 4, 100, 1, ctypes.byref(wide), FAKE_OUT, None) == R
+    rp = B.BraceRarParams(ctypes.sizeof(B.BraceRarParams), 0, 0)
+    assert L.brace_rar_aggregate(FAKE_IN, 4, huge, ctypes.byref(rp), FAKE_OUT, None) == R
+    assert L.brace_aggregate_update(FAKE_IN, 4, huge, 1, pr, 0.1, FAKE_OUT, None) == R
+    assert L.brace_quantize(FAKE_IN, 4, huge, 0, FAKE_OUT, 0, None) == R
+    assert L.brace_vote_packed(FAKE_IN, 4, huge, 0, 1, pr, FAKE_OUT, None) == R
+    assert L.brace_vote_packed(FAKE_IN, 4, (1 << 63) - 1, 0, 1, pr, FAKE_OUT, None) == R
+    assert L.brace_vote_packed_chunk(FAKE_IN, 4, huge, 0, 1, 0, pr, FAKE_OUT, None) == R
+    assert L.brace_consensus_sums(FAKE_IN, 4, huge, 0, pr, FAKE_OUT, None) == R
+    assert L.brace_expand_bits(FAKE_IN, huge, FAKE_OUT, None) == R
+    assert L.brace_apply_bits(FAKE_IN, huge, 0.1, FAKE_OUT, None) == R
+    assert L.brace_packed_row_words((1 << 63) - 1) > 0
+    assert L.brace_packed_row_words(-5) == 0
 
 
 def test_rar_aggregate_rejects_invalid_arguments(L):
