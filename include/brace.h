@@ -69,6 +69,18 @@ typedef struct brace_params {
 void brace_params_init(brace_params_t* params);
 
 /*
+ * Communication volume of one aggregation, the quantity the paper compares (Sec. 2.1,
+ * Sec. 2.2, Sec. 3 and Table 1), for gradients of d dimensions at m bits each over n clients:
+ *   BRACE_COST_SERVER_CLIENT    m*n*d            what the server of a server-client round receives
+ *   BRACE_COST_RING_ALL_REDUCE  2*m*d*(n-1)/n    what one client sends in plain ring-all-reduce
+ *   BRACE_COST_BRACE            d*(n-1)*(m+1)/n  what one client sends in BRACE: m-bit partial
+ *                                                sums in Share-Reduce, 1 bit in Share-Only
+ * Pure host arithmetic.  EINVAL unless 1 <= m <= 64, n >= 1, d >= 0 and the scheme is known.
+ */
+enum { BRACE_COST_SERVER_CLIENT = 0, BRACE_COST_RING_ALL_REDUCE = 1, BRACE_COST_BRACE = 2 };
+int brace_comm_cost(int32_t scheme, int64_t m, int64_t n, int64_t d, double* bits_per_client);
+
+/*
  * Aggregate the whole update: Eq. (1) on every coordinate of every ring chunk,
  * gathered into out_dev[0 .. d).
  *

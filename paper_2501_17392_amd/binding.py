@@ -68,7 +68,7 @@ EXPORTS = (
     "brace_aggregate_update", "brace_aggregate_update_chunk", "brace_expand_bits", "brace_apply_bits",
     "brace_packed_row_words", "brace_quantize", "brace_vote_packed", "brace_vote_packed_chunk",
     "brace_vote_packed_chunks", "brace_aggregate_chunks", "brace_consensus_sums",
-    "brace_set_pointer_checks", "brace_init_device",
+    "brace_set_pointer_checks", "brace_init_device", "brace_comm_cost",
 )
 
 
@@ -136,6 +136,8 @@ def lib():
     L.brace_set_pointer_checks.restype = ctypes.c_int
     L.brace_init_device.argtypes = []
     L.brace_init_device.restype = ctypes.c_int
+    L.brace_comm_cost.argtypes = [ctypes.c_int32, i64, i64, i64, ctypes.POINTER(ctypes.c_double)]
+    L.brace_comm_cost.restype = ctypes.c_int
     rp = ctypes.POINTER(BraceRarParams)
     L.brace_rar_aggregate.argtypes = [vp, i64, i64, rp, vp, vp]
     L.brace_rar_aggregate.restype = ctypes.c_int
@@ -364,6 +366,16 @@ def brace_aggregate_chunks(updates, f: int, chunk_begin: int, chunk_end: int, la
     _check(lib().brace_aggregate_chunks(updates.data_ptr(), n, d, f, chunk_begin, chunk_end,
                                         ctypes.byref(p), _ptr(out), _stream_handle(stream)))
     return out
+
+
+BRACE_COST_SERVER_CLIENT, BRACE_COST_RING_ALL_REDUCE, BRACE_COST_BRACE = 0, 1, 2
+
+
+def brace_comm_cost(scheme: int, m: int, n: int, d: int) -> float:
+    """Bits per round of Table 1 for the given scheme (host arithmetic)."""
+    v = ctypes.c_double()
+    _check(lib().brace_comm_cost(scheme, m, n, d, ctypes.byref(v)))
+    return v.value
 
 
 def brace_init_device():

@@ -894,6 +894,22 @@ int brace_chunk_owner(int64_t n, int64_t chunk, int64_t* owner_client)
     return BRACE_OK;
 }
 
+int brace_comm_cost(int32_t scheme, int64_t m, int64_t n, int64_t d, double* bits_per_client)
+{
+    if (!bits_per_client)
+        return fail(BRACE_EINVAL, "bits_per_client is NULL");
+    if (m < 1 || m > 64 || n < 1 || d < 0)
+        return fail(BRACE_EINVAL, "need 1 <= m <= 64, n >= 1 and d >= 0");
+    const long double M = (long double)m, N = (long double)n, D = (long double)d;
+    switch (scheme) {
+    case BRACE_COST_SERVER_CLIENT: *bits_per_client = (double)(M * N * D); break;
+    case BRACE_COST_RING_ALL_REDUCE: *bits_per_client = (double)(2.0L * M * D * (N - 1.0L) / N); break;
+    case BRACE_COST_BRACE: *bits_per_client = (double)(D * (N - 1.0L) * (M + 1.0L) / N); break;
+    default: return fail(BRACE_EINVAL, "unknown scheme %d", (int)scheme);
+    }
+    return BRACE_OK;
+}
+
 int brace_aggregate(const float* updates_dev, int64_t n, int64_t d, int64_t f,
                     const brace_params_t* params, float* out_dev, void* hip_stream)
 {

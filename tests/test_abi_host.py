@@ -293,6 +293,32 @@ def test_absurd_sizes_are_range_errors_not_overflows(L):
     assert L.brace_packed_row_words(-5) == 0
 
 
+@pytest.mark.parametrize("m,n,d", [(32, 3, 3), (32, 100, 25_000_000), (8, 64, 100_000_000), (1, 1, 0),
+                                   (64, 32767, 1 << 45), (16, 7, 1_000_003)])
+def test_comm_cost_matches_the_closed_forms_of_the_oracle(L, m, n, d):
+    for scheme, ref in ((B.BRACE_COST_SERVER_CLIENT, O.cost_sc), (B.BRACE_COST_RING_ALL_REDUCE, O.cost_rar),
+                        (B.BRACE_COST_BRACE, O.cost_brace)):
+        want = float(ref(m, n, d))
+        got = B.brace_comm_cost(scheme, m, n, d)
+        assert got == pytest.approx(want, rel=1e-15, abs=0.0)
+    # BRACE sends less than plain ring-all-reduce whenever m > 1 (Sec. 3, cost paragraph)
+    if m > 1 and n > 1 and d > 0:
+        assert B.brace_comm_cost(B.BRACE_COST_BRACE, m, n, d) < \
+            B.brace_comm_cost(B.BRACE_COST_RING_ALL_REDUCE, m, n, d)
+
+
+def test_comm_cost_validates(L):
+    v = ctypes.c_double()
+    E = B.BRACE_EINVAL
+    assert L.brace_comm_cost(0, 32, 4, 100, None) == E
+    assert L.brace_comm_cost(3, 32, 4, 100, ctypes.byref(v)) == E
+    assert L.brace_comm_cost(-1, 32, 4, 100, ctypes.byref(v)) == E
+    assert L.brace_comm_cost(0, 0, 4, 100, ctypes.byref(v)) == E
+    assert L.brace_comm_cost(0, 65, 4, 100, ctypes.byref(v)) == E
+    assert L.brace_comm_cost(0, 32, 0, 100, ctypes.byref(v)) == E
+    assert L.brace_comm_cost(0, 32, 4, -1, ctypes.byref(v)) == E
+
+
 def test_rar_aggregate_rejects_invalid_arguments(L):
     def call(inp=FAKE_IN, n=4, d=100, mean=0, ld=0, out=FAKE_OUT, size=None, chunk=None):
         p = B.BraceRarParams(ctypes.sizeof(B.BraceRarParams) if size is None else size, mean, ld)
