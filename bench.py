@@ -276,6 +276,10 @@ def main():
     if not args.no_cpu_baseline:
         log("[bench] timing the CPU oracle on a sample ...")
         result["cpu_baseline"] = cpu_baseline(upd, w, args.lam, out, args.cpu_sample_cols)
+        # reported for context only: the roofline fraction, not this ratio, rates the kernel
+        result["cpu_baseline"]["gpu_over_cpu"] = result["value"] / result["cpu_baseline"]["value"]
+        result["cpu_baseline"]["gpu_over_cpu_1thread"] = \
+            result["value"] / result["cpu_baseline"]["value_1thread"]
         log(f"[bench] oracle: {result['cpu_baseline']['value']:.3e} coords/s on "
             f"{result['cpu_baseline']['cores']} threads; GPU matches oracle on the sample: "
             f"{result['cpu_baseline']['gpu_matches_oracle_on_sample']}")
