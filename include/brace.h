@@ -10,7 +10,7 @@
  * every client holds the same full vector (Phase IV, Share-Only).
  *
  * Here all n clients' flattened updates are resident on one GPU.  The ring is
- * chunk ownership and indexing: the gradient is split in n roughly equal
+ * chunk ownership and indexing: the gradient is split in n about equally long
  * sub-vectors (Sec. 2.2), each chunk is aggregated across the n clients'
  * copies, and the aggregated chunks are written back ("gathered") at their
  * place in the global update.
@@ -117,7 +117,7 @@ int brace_aggregate_chunks(const float* updates_dev, int64_t n, int64_t d, int64
                            float* out_dev, void* hip_stream);
 
 /*
- * Chunk partition (Sec. 2.2: "n roughly equal-sized sub-vectors").  Contiguous, ascending;
+ * Chunk partition (Sec. 2.2: n sub-vectors of about equal size).  Contiguous, ascending;
  * with q = d div n, r = d mod n the first r chunks have q+1 coordinates, the rest q.
  * Host arithmetic only.  [lo, hi) is half-open.
  */

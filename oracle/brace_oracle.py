@@ -16,7 +16,7 @@ What follows the paper, and where:
 * consensus map ................ Sec. 3 Phase III, Eq. (1); restated in
                                  App. A as 2*I(sum > lambda) - 1
 * ring Share-Only .............. Sec. 2.2 Phase II; Sec. 3 Phase IV
-* chunk partition .............. Sec. 2.2 ("n roughly equal-sized sub-vectors")
+* chunk partition .............. Sec. 2.2 (n sub-vectors of about equal size)
 * communication cost ........... Sec. 2.1 (SC), Sec. 2.2 (RAR), Sec. 3 / Table 1
 * Mean rule, model update ...... Sec. 2.1; Sec. 2.2; App. A (update rule)
 
@@ -37,7 +37,7 @@ test, none is pinned by a printed value):
 Pinned by the paper: Eq. (1) itself incl. the tie sum == lambda -> -1, the
 ring direction and chunk ownership (three-client example of Sec. 2.2), the
 attacked sum [22, 1, -185] (Sec. 3), the traffic closed forms (Table 1) and
-"all clients end with the same vector" (Sec. 3 Phase IV).
+the fact that every client ends with the same vector (Sec. 3 Phase IV).
 """
 
 from __future__ import annotations
@@ -55,7 +55,7 @@ import numpy as np
 def chunk_range(n: int, d: int, c: int) -> tuple[int, int]:
     """Half-open coordinate range [lo, hi) of ring chunk c (0-indexed).
 
-    Sec. 2.2 only says the gradient is split in n roughly equal sub-vectors.
+    Sec. 2.2 only asks for n sub-vectors of about the same size.
     Reading: chunks are contiguous and ascending; with q = d div n and
     r = d mod n the first r chunks have q + 1 coordinates, the others q.
     """

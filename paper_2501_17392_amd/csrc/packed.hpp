@@ -1,6 +1,6 @@
 // Quantise-once form of BRACE for gfx950.
 //
-// Sec. 3 Phase I ("1-bit quantization") kept as data: every client's update becomes two
+// Sec. 3 Phase I (the sign quantisation) kept as data: every client's update becomes two
 // bit planes, "x > 0" and "x < 0" (two planes because +-0 and NaN abstain), 2 bits per
 // coordinate instead of 32.  Phases II-IV then run on the planes: the per-coordinate counts
 // of the n clients are kept bit-sliced (one register per counter bit, 32 coordinates per
