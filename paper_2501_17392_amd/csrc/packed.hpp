@@ -25,25 +25,17 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kQuantSpan = 4096;            // coordinates per wave task: 64 loads of 64 lanes
 
-// Phase I for whole rows.  One wave turns 4096 consecutive coordinates of one client into
-// 128 word pairs: a dword load per lane covers 64 coordinates, and the two compares of that
-// load already are the two 64-bit plane masks (one bit per lane).  Lane r keeps the masks
-// of load r, so the wave ends with one 16-byte store per lane, 1 KiB contiguous.
-__global__ void __launch_bounds__(kBlock)
-brace_quantize_kernel(const float* __restrict__ updates, int64_t ld, int64_t d,
-                      uint32_t* __restrict__ signs, int64_t ld_words, int64_t spans_per_row,
-                      int64_t tasks)
+// Phase I for one span: a wave turns 4096 consecutive coordinates of one client (from src,
+// coordinate k0 of a row of d) into 128 word pairs.  A dword load per lane covers 64
+// coordinates, and the two compares of that load already are the two 64-bit plane masks (one
+// bit per lane, held in scalar registers); the masks of load r are written into lane r of
+// the result, so every lane ends with 16 bytes: (pos, neg) of coordinates k0 + 64 r .. + 31
+// and (pos, neg) of the next 32.
+__device__ __forceinline__ u32x4 quantize_span(const float* __restrict__ src, int64_t k0, int64_t d,
+                                               int lane)
 {
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int64_t task = (int64_t)blockIdx.x * kWaves + wave;
-    if (task >= tasks)
-        return;
-    const int64_t row = task / spans_per_row;
-    const int64_t k0 = (task % spans_per_row) * kQuantSpan;
-    const float* src = updates + row * ld + k0;
     const bool full = k0 + kQuantSpan <= d;
-    unsigned long long mine_p = 0, mine_n = 0;
+    uint32_t o0 = 0, o1 = 0, o2 = 0, o3 = 0;
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
         float x[16];
@@ -58,24 +50,44 @@ brace_quantize_kernel(const float* __restrict__ updates, int64_t ld, int64_t d,
                 x[u] = (k < d) ? src[(16 * b + u) * 64 + lane] : 0.0f;
             }
         }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < 16; ++u) {
             const unsigned long long mp = __ballot(x[u] > 0.0f);
             const unsigned long long mn = __ballot(x[u] < 0.0f);
             if (lane == 16 * b + u) {
-                mine_p = mp;
-                mine_n = mn;
+                o0 = (uint32_t)mp;
+                o1 = (uint32_t)mn;
+                o2 = (uint32_t)(mp >> 32);
+                o3 = (uint32_t)(mn >> 32);
             }
         }
     }
+    u32x4 o;
+    o[0] = o0;
+    o[1] = o1;
+    o[2] = o2;
+    o[3] = o3;
+    return o;
+}
+
+// Phase I for whole rows, one span per wave, one 1 KiB store per span.
+__global__ void __launch_bounds__(kBlock)
+brace_quantize_kernel(const float* __restrict__ updates, int64_t ld, int64_t d,
+                      uint32_t* __restrict__ signs, int64_t ld_words, int64_t spans_per_row,
+                      int64_t tasks)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int64_t task = (int64_t)blockIdx.x * kWaves + wave;
+    if (task >= tasks)
+        return;
+    const int64_t row = task / spans_per_row;
+    const int64_t k0 = (task % spans_per_row) * kQuantSpan;
+    const u32x4 o = quantize_span(updates + row * ld + k0, k0, d, lane);
     const int64_t pair = k0 / 32 + 2 * lane;            // first of this lane's two word pairs
     const int64_t pairs = (d + 31) / 32 + (((d + 31) / 32) & 1);   // per row, padded to even
     if (pair < pairs) {
-        u32x4 o;
-        o[0] = (uint32_t)mine_p;
-        o[1] = (uint32_t)mine_n;
-        o[2] = (uint32_t)(mine_p >> 32);
-        o[3] = (uint32_t)(mine_n >> 32);
         // streaming store: 11 % faster than a plain store at n = 100, d = 25 M
         __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(signs + row * ld_words + 2 * pair));
     }
@@ -91,7 +103,7 @@ constexpr int kQuantGroup = 128;            // spans per block: 128 KiB of plane
 // 1.85 ms with a store per span, 1.72 ms with the bursts, 1.40 ms for the reads alone.
 __global__ void __launch_bounds__(kQuantBlock)
 brace_quantize_staged_kernel(const float* __restrict__ updates, int64_t ld, int64_t d,
-                      uint32_t* __restrict__ signs, int64_t ld_words, int64_t groups_per_row)
+                             uint32_t* __restrict__ signs, int64_t ld_words, int64_t groups_per_row)
 {
     extern __shared__ unsigned char lds_raw[];
     u32x4* stage = reinterpret_cast<u32x4*>(lds_raw);           // kQuantGroup x 64 entries
@@ -107,39 +119,8 @@ brace_quantize_staged_kernel(const float* __restrict__ updates, int64_t ld, int6
         if (span >= spans)
             break;                                              // wave-uniform; barrier is below
         const int64_t k0 = span * kQuantSpan;
-        const float* src = rowp + k0;
-        const bool full = k0 + kQuantSpan <= d;
-        unsigned long long mine_p = 0, mine_n = 0;
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            float x[16];
-            if (full) {
-#pragma unroll
-                for (int u = 0; u < 16; ++u)
-                    x[u] = __builtin_nontemporal_load(src + (16 * b + u) * 64 + lane);
-            } else {
-#pragma unroll
-                for (int u = 0; u < 16; ++u) {
-                    const int64_t k = k0 + (16 * b + u) * 64 + lane;
-                    x[u] = (k < d) ? src[(16 * b + u) * 64 + lane] : 0.0f;
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < 16; ++u) {
-                const unsigned long long mp = __ballot(x[u] > 0.0f);
-                const unsigned long long mn = __ballot(x[u] < 0.0f);
-                if (lane == 16 * b + u) {
-                    mine_p = mp;
-                    mine_n = mn;
-                }
-            }
-        }
-        u32x4 o;
-        o[0] = (uint32_t)mine_p;
-        o[1] = (uint32_t)mine_n;
-        o[2] = (uint32_t)(mine_p >> 32);
-        o[3] = (uint32_t)(mine_n >> 32);
-        stage[local * 64 + lane] = o;           // lane's two word pairs: coordinates k0 + 64*lane ..
+        // lane's two word pairs: coordinates k0 + 64 * lane ..
+        stage[local * 64 + lane] = quantize_span(rowp + k0, k0, d, lane);
     }
     __syncthreads();
     // Entry e of the group = word pairs 2e, 2e+1 counted from the group's first pair.
