@@ -29,6 +29,8 @@ test, none is pinned by a printed value):
   coordinate than the rest.                              [parity unpinned]
 * packed output: bit j of byte b is coordinate 8*b + j, 1 means +1.
                                                          [parity unpinned]
+* one-bit form (vote_plane): bit = 1 where the vote is +1, LSB first, rows padded
+  to 16 bytes; same status as the two-plane layout below.   [parity unpinned]
 * bit planes of the quantise-once form (sign_planes): per client, word pair j
   = ("x > 0" bits, "x < 0" bits) of coordinates 32j .. 32j+31, LSB first, rows
   padded to an even number of pairs.  A storage convention of this build, not
@@ -361,6 +363,43 @@ def brace_from_planes(planes: np.ndarray, d: int, lam: float, zero_sign: int = 0
 # --------------------------------------------------------------------------
 # signSGD run over the same four phases (Sec. 5.2): plain majority vote
 # --------------------------------------------------------------------------
+
+def vote_plane_row_words(d: int) -> int:
+    """32-bit words per client row of the one-bit form, padded to 16 bytes."""
+    w = (d + 31) // 32
+    return (w + 3) // 4 * 4
+
+
+def vote_plane(updates: np.ndarray, zero_sign: int) -> np.ndarray:
+    """Sec. 3 Phase I as the paper words it, one bit per dimension: bit = 1 where the client's
+    quantised vote is +1.  Only defined when every coordinate votes, i.e. zero_sign = +1 or -1
+    (with zero_sign = 0 a zero abstains and one bit cannot say so).
+
+    Returns uint32 of shape (n, vote_plane_row_words(d)); bit b of word j <-> coordinate
+    32j + b; padding bits are zero.
+    """
+    if zero_sign not in (-1, 1):
+        raise ValueError("the one-bit form needs zero_sign = +1 or -1")
+    updates = np.asarray(updates)
+    n, d = updates.shape
+    words = vote_plane_row_words(d)
+    padded = np.zeros((n, words * 32), dtype=np.uint8)
+    padded[:, :d] = sign_quantize(updates, zero_sign) > 0
+    packed = np.packbits(padded, axis=1, bitorder="little")            # bytes, LSB first
+    return packed.view("<u4").reshape(n, words).astype(np.uint32)
+
+
+def brace_from_vote_plane(plane: np.ndarray, d: int, lam: float) -> BraceResult:
+    """Phases II-IV from the one-bit votes: with P clients voting +1 out of n, the sign-sum is
+    S = P - (n - P) = 2P - n, then Eq. (1)."""
+    plane = np.asarray(plane, dtype=np.uint32)
+    n = plane.shape[0]
+    as_bytes = np.ascontiguousarray(plane).astype("<u4").view(np.uint8).reshape(n, -1)
+    ups = np.unpackbits(as_bytes, axis=1, bitorder="little")[:, :d].astype(np.int64)
+    sums = 2 * ups.sum(axis=0) - n
+    out = consensus(sums, lam)
+    return BraceResult(out=out, sums=sums, bits=pack_bits(out))
+
 
 def signsgd_majority(updates: np.ndarray, zero_sign: int = 0) -> np.ndarray:
     """sign(sum_i sign(g_i[k])) in {-1, 0, +1} as float32: Phase III replaced by the plain

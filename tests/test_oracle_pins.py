@@ -574,3 +574,37 @@ def test_majority_rule_relation_to_eq_1():
         assert (brace0[S == 0] == -1).all()
     G = rng.standard_normal((9, 300)).astype(np.float32)      # odd n, no zeros: median sign
     assert np.array_equal(O.signsgd_majority(G), np.sign(np.median(G, axis=0)).astype(np.float32))
+
+
+# --------------------------------------------------------------------------
+# One-bit form of Phase I (every coordinate votes: zero_sign = +1 or -1)
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("zero_sign", [1, -1])
+def test_one_bit_votes_reproduce_the_definition(zero_sign):
+    rng = np.random.default_rng(5 + zero_sign)
+    for n, d in ((1, 1), (3, 31), (4, 32), (5, 33), (7, 130), (9, 1000)):
+        g = rng.standard_normal((n, d)).astype(np.float32)
+        g[rng.random((n, d)) < 0.2] = 0.0
+        g[rng.random((n, d)) < 0.1] = -0.0
+        g[rng.random((n, d)) < 0.05] = np.nan
+        plane = O.vote_plane(g, zero_sign)
+        assert plane.shape == (n, O.vote_plane_row_words(d)) and plane.shape[1] % 4 == 0
+        # bit by bit against the quantised votes, padding zero
+        for i in range(n):
+            for k in range(d):
+                bit = (int(plane[i, k // 32]) >> (k % 32)) & 1
+                assert bit == int(O.sign_quantize(g[i:i + 1, k:k + 1], zero_sign)[0, 0] > 0)
+        unpacked = np.unpackbits(plane.view(np.uint8).reshape(n, -1), axis=1, bitorder="little")
+        assert not unpacked[:, d:].any()
+        for lam in (-n - 1, -1, 0, 0.5, 1, 2, n):
+            got = O.brace_from_vote_plane(plane, d, lam)
+            want = O.brace_direct(g, lam, zero_sign)
+            assert np.array_equal(got.out, want.out)
+            assert np.array_equal(got.sums, want.sums)
+            assert np.array_equal(got.bits, want.bits)
+
+
+def test_one_bit_form_refuses_abstaining_zeros():
+    with pytest.raises(ValueError):
+        O.vote_plane(np.zeros((2, 4), dtype=np.float32), 0)
