@@ -212,6 +212,8 @@ def main():
         rw = B.brace_packed_row_words(w.d)
         signs = torch.empty(w.n, rw, device=dev, dtype=torch.int32)
         model = torch.zeros(w.d, device=dev, dtype=torch.float32)
+        vw = B.brace_1bit_row_words(w.d)
+        votes = torch.empty(w.n, vw, device=dev, dtype=torch.int32)
         # 8 partial sign-sums (one per device of an 8-device ring), values as 12-13 clients give
         parts = torch.randint(-13, 14, (8, w.d), device=dev, dtype=torch.int16)
         nd4 = 4 * w.n * w.d
@@ -231,6 +233,10 @@ def main():
              4 * w.d + 4 * ((w.d + 31) // 32)),
             ("apply_bits", lambda: B.brace_apply_bits(bits, w.d, 1e-3, model, stream=stream),
              8 * w.d + 4 * ((w.d + 31) // 32)),
+            ("quantize_1bit", lambda: B.brace_quantize_1bit(upd, 1, votes, stream=stream),
+             nd4 + 4 * w.n * vw),
+            ("vote_1bit", lambda: B.brace_vote_1bit(votes, w.d, w.f, args.lam, out=out, stream=stream),
+             4 * w.n * vw + 4 * w.d + 2 * 4 * ((w.d + 31) // 32)),
             ("consensus_sums_g8", lambda: B.brace_consensus_sums(parts, args.lam, out=out,
                                                                  stream=stream),
              2 * 8 * w.d + 4 * w.d),

@@ -187,6 +187,28 @@ int brace_vote_packed_chunks(const uint32_t* signs_dev, int64_t n, int64_t d, in
                              const brace_params_t* params, float* out_dev, void* hip_stream);
 
 /*
+ * One-bit form of the quantise-once route, for rules in which every coordinate votes
+ * (zero_sign = +1 or -1): then a client's quantised update is exactly one bit per dimension,
+ * the format whose volume the cost analysis of Sec. 3 counts.  brace_quantize_1bit writes
+ * bit = 1 where the client's vote is +1 (zero_sign = +1: everything but x < 0; zero_sign = -1:
+ * only x > 0); it returns BRACE_EINVAL for zero_sign = 0, where a zero abstains and the
+ * two-plane form above is needed.  brace_vote_1bit runs Phases II-IV on those bits: with P
+ * votes of +1 among n the sign-sum is 2P - n, then Eq. (1); the result equals brace_aggregate
+ * on the floats with the same zero_sign.  It honours lambda and out_bits_dev of params
+ * (zero_sign and ld are not used, rule must be 0, sums_dev NULL).
+ *
+ * Layout: client i's row at votes_dev + i*ld_words (uint32 words), bit b of word j <->
+ * coordinate 32j + b, brace_1bit_row_words(d) = roundup(ceil(d/32), 4) words per row, padding
+ * bits zero; ld_words = 0 means exactly that, otherwise a multiple of 4 at least that.
+ * votes_dev and out_dev 16-byte aligned; votes_dev must not overlap updates_dev.
+ */
+int64_t brace_1bit_row_words(int64_t d);
+int brace_quantize_1bit(const float* updates_dev, int64_t n, int64_t d, int64_t ld, int32_t zero_sign,
+                        uint32_t* votes_dev, int64_t ld_words, void* hip_stream);
+int brace_vote_1bit(const uint32_t* votes_dev, int64_t n, int64_t d, int64_t ld_words, int64_t f,
+                    const brace_params_t* params, float* out_dev, void* hip_stream);
+
+/*
  * Sec. 3 Phase III on its own, for an owner that holds partial sign-sums: in Share-Reduce
  * (Phase II) what travels are partial sums of signs (m bits per dimension in the cost
  * analysis of Sec. 3).  parts_dev[j][k], j in [0, g), are g such partial sums as int16 (row

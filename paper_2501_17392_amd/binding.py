@@ -69,6 +69,7 @@ EXPORTS = (
     "brace_packed_row_words", "brace_quantize", "brace_vote_packed", "brace_vote_packed_chunk",
     "brace_vote_packed_chunks", "brace_aggregate_chunks", "brace_consensus_sums",
     "brace_set_pointer_checks", "brace_init_device", "brace_comm_cost",
+    "brace_1bit_row_words", "brace_quantize_1bit", "brace_vote_1bit",
 )
 
 
@@ -138,6 +139,12 @@ def lib():
     L.brace_init_device.restype = ctypes.c_int
     L.brace_comm_cost.argtypes = [ctypes.c_int32, i64, i64, i64, ctypes.POINTER(ctypes.c_double)]
     L.brace_comm_cost.restype = ctypes.c_int
+    L.brace_1bit_row_words.argtypes = [i64]
+    L.brace_1bit_row_words.restype = i64
+    L.brace_quantize_1bit.argtypes = [vp, i64, i64, i64, ctypes.c_int32, vp, i64, vp]
+    L.brace_quantize_1bit.restype = ctypes.c_int
+    L.brace_vote_1bit.argtypes = [vp, i64, i64, i64, i64, pp, vp, vp]
+    L.brace_vote_1bit.restype = ctypes.c_int
     rp = ctypes.POINTER(BraceRarParams)
     L.brace_rar_aggregate.argtypes = [vp, i64, i64, rp, vp, vp]
     L.brace_rar_aggregate.restype = ctypes.c_int
@@ -343,6 +350,29 @@ def brace_vote_packed_chunks(signs, d: int, f: int, chunk_begin: int, chunk_end:
     p = make_params(lam, zero_sign, 0, _ptr(out_bits), None)
     _check(lib().brace_vote_packed_chunks(signs.data_ptr(), n, d, ld_words, f, chunk_begin, chunk_end,
                                           ctypes.byref(p), _ptr(out), _stream_handle(stream)))
+    return out
+
+
+def brace_1bit_row_words(d: int) -> int:
+    return int(lib().brace_1bit_row_words(d))
+
+
+def brace_quantize_1bit(updates, zero_sign: int, votes, stream=None):
+    """Phase I as one bit per dimension (zero_sign = +1 or -1): bit = 1 where the vote is +1."""
+    n, d, ld = _matrix(updates)
+    ld_words = votes.stride(0) if n > 1 else 0
+    _check(lib().brace_quantize_1bit(updates.data_ptr(), n, d, ld, int(zero_sign), _ptr(votes),
+                                     ld_words, _stream_handle(stream)))
+    return votes
+
+
+def brace_vote_1bit(votes, d: int, f: int, lam: float = 5.0, out=None, out_bits=None, stream=None):
+    """Phases II-IV on the one-bit votes; equals brace_aggregate with the zero_sign they were made with."""
+    n = votes.shape[0]
+    ld_words = votes.stride(0) if n > 1 else 0
+    p = make_params(lam, 0, 0, _ptr(out_bits), None)
+    _check(lib().brace_vote_1bit(votes.data_ptr(), n, d, ld_words, f, ctypes.byref(p), _ptr(out),
+                                 _stream_handle(stream)))
     return out
 
 

@@ -1333,6 +1333,169 @@ int brace_vote_packed_chunk(const uint32_t* signs_dev, int64_t n, int64_t d, int
                                     hip_stream);
 }
 
+int64_t brace_1bit_row_words(int64_t d)
+{
+    if (d < 0)
+        return 0;
+    const int64_t w = d / 32 + (d % 32 != 0);
+    return w / 4 * 4 + (w % 4 ? 4 : 0);
+}
+
+int brace_quantize_1bit(const float* updates_dev, int64_t n, int64_t d, int64_t ld, int32_t zero_sign,
+                        uint32_t* votes_dev, int64_t ld_words, void* hip_stream)
+{
+    if (n < 1 || d < 0)
+        return fail(BRACE_EINVAL, "need n >= 1 and d >= 0");
+    if (n > BRACE_MAX_CLIENTS)
+        return fail(BRACE_ERANGE, "n = %lld exceeds BRACE_MAX_CLIENTS", (long long)n);
+    if (zero_sign != 1 && zero_sign != -1)
+        return fail(BRACE_EINVAL, "the one-bit form needs zero_sign = +1 or -1 (a zero that abstains "
+                                  "needs the two-plane form)");
+    if (ld == 0)
+        ld = d;
+    if (ld < d)
+        return fail(BRACE_EINVAL, "ld = %lld is smaller than d = %lld", (long long)ld, (long long)d);
+    if (check_extent(n, ld, 4) != BRACE_OK)
+        return BRACE_ERANGE;
+    const int64_t row_words = brace_1bit_row_words(d);
+    if (ld_words == 0)
+        ld_words = row_words;
+    if (ld_words < row_words || (ld_words & 3))
+        return fail(BRACE_EINVAL, "ld_words must be a multiple of 4 and >= brace_1bit_row_words(d)");
+    if (check_extent(n, ld_words, 4) != BRACE_OK)
+        return BRACE_ERANGE;
+    if (d == 0)
+        return BRACE_OK;
+    if (!updates_dev || !votes_dev || !aligned_to(updates_dev, 4) || !aligned_to(votes_dev, 16))
+        return fail(BRACE_EINVAL, "updates_dev (4-byte aligned) and votes_dev (16-byte aligned) "
+                                  "must be non-NULL");
+    {
+        const char* in_lo = reinterpret_cast<const char*>(updates_dev);
+        const char* in_hi = in_lo + ((n - 1) * ld + d) * 4;
+        const char* out_lo = reinterpret_cast<const char*>(votes_dev);
+        const char* out_hi = out_lo + ((n - 1) * ld_words + row_words) * 4;
+        if (out_lo < in_hi && in_lo < out_hi)
+            return fail(BRACE_EINVAL, "votes_dev overlaps updates_dev");
+    }
+    int rc = check_device_range(updates_dev, ((n - 1) * ld + d) * 4, "updates_dev");
+    if (rc == BRACE_OK)
+        rc = check_device_range(votes_dev, ((n - 1) * ld_words + row_words) * 4, "votes_dev");
+    if (rc != BRACE_OK)
+        return rc;
+    const int64_t spans = (d + kQuantSpan - 1) / kQuantSpan;
+    const int64_t groups = (spans + kVoteGroup - 1) / kVoteGroup;       // per row
+    const brace_tuning_t t = g_tuning;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int up = zero_sign == 1 ? 1 : 0;
+    // Same rule as the two-plane kernel: bursts when the blocks come in well filled rounds.
+    const int64_t cus = compute_units() > 0 ? compute_units() : 256;
+    const int64_t blocks = groups * n;
+    const double fill = (double)blocks / (double)((blocks + cus - 1) / cus * cus);
+    const bool staged = t.stage_writes == 2 ||
+                        (t.stage_writes == 0 && spans >= kVoteGroup && blocks >= 4 * cus &&
+                         fill >= 0.9);
+    if (staged) {
+        if (blocks > 0x7fffffffLL)
+            return fail(BRACE_ERANGE, "matrix too large for one launch");
+        constexpr size_t lds = (size_t)kVoteGroup * 64 * sizeof(u32x2);
+        static_assert(lds <= kStageBytes, "vote stage exceeds the LDS opted in to");
+        rc = allow_stage_lds(reinterpret_cast<const void*>(brace_quantize_1bit_staged_kernel));
+        if (rc != BRACE_OK)
+            return rc;
+        hipLaunchKernelGGL(brace_quantize_1bit_staged_kernel, dim3((unsigned)blocks),
+                           dim3(kQuantBlock), lds, stream, updates_dev, ld, d, votes_dev, ld_words,
+                           row_words, groups, up);
+        return check_launch("staged one-bit quantize kernel");
+    }
+    const int64_t tasks = spans * n;
+    const int64_t grid = (tasks + kWaves - 1) / kWaves;
+    if (grid > 0x7fffffffLL)
+        return fail(BRACE_ERANGE, "matrix too large for one launch");
+    hipLaunchKernelGGL(brace_quantize_1bit_kernel, dim3((unsigned)grid), dim3(kBlock), 0, stream,
+                       updates_dev, ld, d, votes_dev, ld_words, row_words, spans, tasks, up);
+    return check_launch("one-bit quantize kernel");
+}
+
+int brace_vote_1bit(const uint32_t* votes_dev, int64_t n, int64_t d, int64_t ld_words, int64_t f,
+                    const brace_params_t* params, float* out_dev, void* hip_stream)
+{
+    if (!params)
+        return fail(BRACE_EINVAL, "params is NULL");
+    if (params->struct_size != sizeof(brace_params_t))
+        return fail(BRACE_EINVAL, "params->struct_size is %u, expected %zu", params->struct_size,
+                    sizeof(brace_params_t));
+    if (n < 1 || d < 0 || f < 0 || f > n)
+        return fail(BRACE_EINVAL, "need n >= 1, d >= 0 and 0 <= f <= n");
+    if (n > BRACE_MAX_CLIENTS)
+        return fail(BRACE_ERANGE, "n = %lld exceeds BRACE_MAX_CLIENTS", (long long)n);
+    if (!std::isfinite(params->lambda))
+        return fail(BRACE_EINVAL, "lambda must be finite");
+    if (params->rule != 0 || params->sums_dev)
+        return fail(BRACE_EINVAL, "the one-bit vote implements rule 0 and produces no sign-sums");
+    if (d > ((int64_t)1 << 45))
+        return fail(BRACE_ERANGE, "d = %lld does not fit the address space", (long long)d);
+    const int64_t row_words = brace_1bit_row_words(d);
+    if (ld_words == 0)
+        ld_words = row_words;
+    if (ld_words < row_words || (ld_words & 3))
+        return fail(BRACE_EINVAL, "ld_words must be a multiple of 4 and >= brace_1bit_row_words(d)");
+    if (check_extent(n, ld_words, 4) != BRACE_OK)
+        return BRACE_ERANGE;
+    if (d == 0)
+        return BRACE_OK;
+    uint32_t* bits = static_cast<uint32_t*>(params->out_bits_dev);
+    if (!votes_dev || !aligned_to(votes_dev, 16))
+        return fail(BRACE_EINVAL, "votes_dev must be non-NULL and 16-byte aligned");
+    if (!out_dev && !bits)
+        return fail(BRACE_EINVAL, "no output: out_dev and out_bits_dev are both NULL");
+    if (out_dev && !aligned_to(out_dev, 16))
+        return fail(BRACE_EINVAL, "out_dev must be 16-byte aligned for the one-bit vote");
+    if (bits && !aligned_to(bits, 4))
+        return fail(BRACE_EINVAL, "out_bits_dev must be 4-byte aligned");
+
+    const double fl = std::floor((double)params->lambda);
+    const int ni = (int)n;
+    int thresh;
+    if (fl >= (double)n)
+        thresh = ni + 1;
+    else if (fl < -(double)n - 1.0)
+        thresh = -ni;
+    else
+        thresh = (int)fl + 1;
+    // S = 2P - n >= thresh  <=>  P >= ceil((n + thresh) / 2); n + thresh is in [0, 2n + 1].
+    const int q = (ni + thresh + 1) / 2;
+
+    int rc = check_device_range(votes_dev, ((n - 1) * ld_words + row_words) * 4, "votes_dev");
+    if (rc == BRACE_OK)
+        rc = check_device_range(out_dev, d * 4, "out_dev");
+    if (rc == BRACE_OK)
+        rc = check_device_range(bits, ((d + 31) / 32) * 4, "out_bits_dev");
+    if (rc != BRACE_OK)
+        return rc;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int64_t cols4 = row_words / 4;
+    const int64_t grid = (cols4 + kBlock - 1) / kBlock;
+    if (grid > 0x7fffffffLL)
+        return fail(BRACE_ERANGE, "vector too long for one launch");
+    uint32_t* dst = bits ? bits : reinterpret_cast<uint32_t*>(out_dev);
+    const int scratch = bits ? 0 : 1;
+    const u32x4* planes = reinterpret_cast<const u32x4*>(votes_dev);
+    if (n <= 255)
+        hipLaunchKernelGGL(brace_vote_1bit_kernel<8>, dim3((unsigned)grid), dim3(kBlock), 0, stream,
+                           planes, ld_words / 4, ni, cols4, q, dst, scratch, d);
+    else
+        hipLaunchKernelGGL(brace_vote_1bit_kernel<16>, dim3((unsigned)grid), dim3(kBlock), 0, stream,
+                           planes, ld_words / 4, ni, cols4, q, dst, scratch, d);
+    rc = check_launch("one-bit vote kernel");
+    if (rc != BRACE_OK || !out_dev)
+        return rc;
+    const int64_t groups = (d + kGroup - 1) / kGroup;
+    const int64_t egrid = (groups + kWaves - 1) / kWaves;
+    hipLaunchKernelGGL(brace_expand_kernel, dim3((unsigned)egrid), dim3(kBlock), 0, stream, out_dev,
+                       static_cast<const uint32_t*>(bits), (int64_t)0, groups, d);
+    return check_launch("expand kernel");
+}
+
 int brace_consensus_sums(const int16_t* parts_dev, int64_t g, int64_t d, int64_t ld,
                          const brace_params_t* params, float* out_dev, void* hip_stream)
 {
@@ -1513,7 +1676,10 @@ int brace_init_device(void)
                 if (rc != BRACE_OK)
                     return rc;
             }
-    return allow_stage_lds(reinterpret_cast<const void*>(brace_quantize_staged_kernel));
+    const int rc = allow_stage_lds(reinterpret_cast<const void*>(brace_quantize_staged_kernel));
+    if (rc != BRACE_OK)
+        return rc;
+    return allow_stage_lds(reinterpret_cast<const void*>(brace_quantize_1bit_staged_kernel));
 }
 
 int brace_set_pointer_checks(int32_t enabled)

@@ -257,4 +257,186 @@ brace_vote_packed_kernel(const u32x4* __restrict__ signs, int64_t ld4, int n, in
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// One-bit form: when every coordinate votes (zero_sign = +1 or -1) a client's quantised
+// update is one bit per dimension, bit = 1 <=> the vote is +1, which is the wire format the
+// cost analysis of Sec. 3 counts.  Row i at votes + i*ld_words, bit b of word j <->
+// coordinate 32j + b, rows padded with zero bits to a multiple of 4 words.
+// ---------------------------------------------------------------------------------------
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// One span (4096 coordinates) of one client: the ballot of load r is the 64-bit mask of
+// coordinates k0 + 64 r .. + 63 and ends in lane r, 8 bytes per lane, 512 bytes per span.
+// up_if_not_negative: zero_sign = +1 (only x < 0 votes -1); else zero_sign = -1 (only x > 0
+// votes +1).  Coordinates past d read as a -1 vote, i.e. a zero padding bit.
+__device__ __forceinline__ u32x2 vote_span(const float* __restrict__ src, int64_t k0, int64_t d,
+                                           int lane, bool up_if_not_negative)
+{
+    const bool full = k0 + kQuantSpan <= d;
+    const float pad = up_if_not_negative ? -1.0f : 0.0f;
+    uint32_t o0 = 0, o1 = 0;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        float x[16];
+        if (full) {
+#pragma unroll
+            for (int u = 0; u < 16; ++u)
+                x[u] = __builtin_nontemporal_load(src + (16 * b + u) * 64 + lane);
+        } else {
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int64_t k = k0 + (16 * b + u) * 64 + lane;
+                x[u] = (k < d) ? src[(16 * b + u) * 64 + lane] : pad;
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const unsigned long long m =
+                up_if_not_negative ? __ballot(!(x[u] < 0.0f)) : __ballot(x[u] > 0.0f);
+            if (lane == 16 * b + u) {
+                o0 = (uint32_t)m;
+                o1 = (uint32_t)(m >> 32);
+            }
+        }
+    }
+    u32x2 o;
+    o[0] = o0;
+    o[1] = o1;
+    return o;
+}
+
+// One span per wave, one 512-byte store per span.
+__global__ void __launch_bounds__(kBlock)
+brace_quantize_1bit_kernel(const float* __restrict__ updates, int64_t ld, int64_t d,
+                           uint32_t* __restrict__ votes, int64_t ld_words, int64_t row_words,
+                           int64_t spans_per_row, int64_t tasks, int up_if_not_negative)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int64_t task = (int64_t)blockIdx.x * kWaves + wave;
+    if (task >= tasks)
+        return;
+    const int64_t row = task / spans_per_row;
+    const int64_t k0 = (task % spans_per_row) * kQuantSpan;
+    const u32x2 o = vote_span(updates + row * ld + k0, k0, d, lane, up_if_not_negative != 0);
+    const int64_t word = k0 / 32 + 2 * lane;            // first of this lane's two words
+    if (word < row_words)                               // row_words is even
+        __builtin_nontemporal_store(o, reinterpret_cast<u32x2*>(votes + row * ld_words + word));
+}
+
+constexpr int kVoteGroup = 256;             // spans per block of the burst variant: 128 KiB of votes
+
+// Long rows: a block owns 256 adjacent spans of one row, parks their votes in LDS and writes
+// one contiguous burst of 128 KiB.
+__global__ void __launch_bounds__(kQuantBlock)
+brace_quantize_1bit_staged_kernel(const float* __restrict__ updates, int64_t ld, int64_t d,
+                                  uint32_t* __restrict__ votes, int64_t ld_words, int64_t row_words,
+                                  int64_t groups_per_row, int up_if_not_negative)
+{
+    extern __shared__ unsigned char lds_raw[];
+    u32x2* stage = reinterpret_cast<u32x2*>(lds_raw);           // kVoteGroup x 64 entries
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int64_t row = (int64_t)blockIdx.x / groups_per_row;
+    const int64_t span0 = ((int64_t)blockIdx.x % groups_per_row) * kVoteGroup;
+    const int64_t spans = (d + kQuantSpan - 1) / kQuantSpan;    // per row
+    const float* rowp = updates + row * ld;
+    for (int it = 0; it < kVoteGroup / kQuantWaves; ++it) {
+        const int local = it * kQuantWaves + wave;
+        const int64_t span = span0 + local;
+        if (span >= spans)
+            break;                                              // wave-uniform; barrier is below
+        const int64_t k0 = span * kQuantSpan;
+        stage[local * 64 + lane] = vote_span(rowp + k0, k0, d, lane, up_if_not_negative != 0);
+    }
+    __syncthreads();
+    // Entry e of the group = words 4e .. 4e+3 counted from the group's first word.
+    const int64_t word0 = span0 * (kQuantSpan / 32);
+    const u32x4* st4 = reinterpret_cast<const u32x4*>(lds_raw);
+    u32x4* dst = reinterpret_cast<u32x4*>(votes + row * ld_words + word0);
+    int64_t entries = (row_words - word0) / 4;                  // row_words is a multiple of 4
+    if (entries > (int64_t)kVoteGroup * 32)
+        entries = (int64_t)kVoteGroup * 32;
+    for (int64_t e = threadIdx.x; e < entries; e += kQuantBlock)
+        __builtin_nontemporal_store(st4[e], dst + e);
+}
+
+// Phases II-IV on one-bit votes.  One lane owns 4 adjacent words (128 coordinates); cnt[b] is
+// bit b of the running count P of +1 votes, eight clients per carry-save tree as above.
+// S = 2P - n, so S >= thresh <=> P - q >= 0 with q = ceil((n + thresh) / 2) from the host.
+template <int B>
+__global__ void __launch_bounds__(kBlock)
+brace_vote_1bit_kernel(const u32x4* __restrict__ votes, int64_t ld4, int n, int64_t cols4, int q,
+                       uint32_t* __restrict__ dst, int scratch_layout, int64_t d)
+{
+    const int64_t col = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (col >= cols4)
+        return;
+    u32x4 cnt[B];
+#pragma unroll
+    for (int b = 0; b < B; ++b)
+        cnt[b] = (u32x4)(0u);
+    const uint32_t lane = threadIdx.x & 63;
+    const int64_t col0 = __builtin_amdgcn_readfirstlane((int)((col - lane) >> 6)) * (int64_t)64;
+    const u32x4* p = votes + col0;
+    int i = 0;
+    for (; i + 8 <= n; i += 8) {
+        u32x4 a[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r)
+            a[r] = __builtin_nontemporal_load(scalar_ptr(p + (int64_t)r * ld4) + lane);
+        __builtin_amdgcn_sched_barrier(0);
+        u32x4 twos_a, twos_b, fours_a, fours_b, eights;
+        csa(twos_a, cnt[0], cnt[0], a[0], a[1]);
+        csa(twos_b, cnt[0], cnt[0], a[2], a[3]);
+        csa(fours_a, cnt[1], cnt[1], twos_a, twos_b);
+        csa(twos_a, cnt[0], cnt[0], a[4], a[5]);
+        csa(twos_b, cnt[0], cnt[0], a[6], a[7]);
+        csa(fours_b, cnt[1], cnt[1], twos_a, twos_b);
+        csa(eights, cnt[2], cnt[2], fours_a, fours_b);
+        u32x4 carry = eights;
+#pragma unroll
+        for (int b = 3; b < B; ++b) {
+            const u32x4 t = cnt[b] & carry;
+            cnt[b] ^= carry;
+            carry = t;
+        }
+        p += 8 * ld4;
+    }
+    for (; i < n; ++i) {
+        u32x4 carry = scalar_ptr(p)[lane];
+#pragma unroll
+        for (int b = 0; b < B; ++b) {
+            const u32x4 t = cnt[b] & carry;
+            cnt[b] ^= carry;
+            carry = t;
+        }
+        p += ld4;
+    }
+    // P - q on B + 2 bit slices (P >= 0, so its higher bits are zero); the top bit is the sign.
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        uint32_t borrow = 0, top = 0;
+#pragma unroll
+        for (int b = 0; b < B + 2; ++b) {
+            const uint32_t x = (b < B) ? cnt[b][e] : 0u;
+            const uint32_t y = ((q >> b) & 1) ? ~0u : 0u;
+            const uint32_t u = x ^ y;
+            top = u ^ borrow;
+            borrow = (~x & y) | (~u & borrow);
+        }
+        uint32_t result = ~top;                 // bit set <=> P - q >= 0 <=> +1
+        const int64_t k = (4 * col + e) * 32;   // first coordinate of this word
+        if (k >= d)
+            continue;
+        if (d - k < 32)
+            result &= (1u << (d - k)) - 1u;     // padding bits stay zero
+        if (scratch_layout)
+            dst[scratch_word(k)] = result;
+        else
+            dst[k >> 5] = result;
+    }
+}
+
 }  // namespace brace_dev

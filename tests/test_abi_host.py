@@ -319,6 +319,39 @@ def test_comm_cost_validates(L):
     assert L.brace_comm_cost(0, 32, 4, -1, ctypes.byref(v)) == E
 
 
+def test_one_bit_entry_points_validate(L):
+    E, R = B.BRACE_EINVAL, B.BRACE_ERANGE
+    p = B.make_params(5.0)
+    pr = ctypes.byref(p)
+    for d in (0, 1, 31, 32, 33, 127, 128, 129, 1000, 25_000_000):
+        assert L.brace_1bit_row_words(d) == O.vote_plane_row_words(d)
+    assert L.brace_1bit_row_words(-3) == 0 and L.brace_1bit_row_words((1 << 63) - 1) > 0
+    assert L.brace_quantize_1bit(FAKE_IN, 4, 100, 0, 0, FAKE_OUT, 0, None) == E       # zeros abstain
+    assert b"two-plane" in L.brace_last_error()
+    assert L.brace_quantize_1bit(FAKE_IN, 4, 100, 0, 2, FAKE_OUT, 0, None) == E
+    assert L.brace_quantize_1bit(None, 4, 100, 0, 1, FAKE_OUT, 0, None) == E
+    assert L.brace_quantize_1bit(FAKE_IN, 4, 100, 0, 1, None, 0, None) == E
+    assert L.brace_quantize_1bit(FAKE_IN, 4, 100, 0, 1, FAKE_OUT + 8, 0, None) == E
+    assert L.brace_quantize_1bit(FAKE_IN, 4, 100, 50, 1, FAKE_OUT, 0, None) == E
+    assert L.brace_quantize_1bit(FAKE_IN, 4, 100, 0, 1, FAKE_OUT, 2, None) == E
+    assert L.brace_quantize_1bit(FAKE_IN, 4, 100, 0, 1, FAKE_OUT, 6, None) == E
+    assert L.brace_quantize_1bit(FAKE_IN, 4, 100, 0, 1, FAKE_IN + 64, 0, None) == E   # overlap
+    assert L.brace_quantize_1bit(FAKE_IN, 0, 100, 0, 1, FAKE_OUT, 0, None) == E
+    assert L.brace_quantize_1bit(FAKE_IN, B.BRACE_MAX_CLIENTS + 1, 100, 0, 1, FAKE_OUT, 0, None) == R
+    assert L.brace_quantize_1bit(FAKE_IN, 4, 1 << 62, 0, 1, FAKE_OUT, 0, None) == R
+    assert L.brace_quantize_1bit(None, 4, 0, 0, -1, None, 0, None) == B.BRACE_OK
+    assert L.brace_vote_1bit(FAKE_IN, 4, 100, 0, 1, None, FAKE_OUT, None) == E
+    assert L.brace_vote_1bit(None, 4, 100, 0, 1, pr, FAKE_OUT, None) == E
+    assert L.brace_vote_1bit(FAKE_IN, 4, 100, 0, 1, pr, None, None) == E
+    assert L.brace_vote_1bit(FAKE_IN, 4, 100, 0, 1, pr, FAKE_OUT + 4, None) == E
+    assert L.brace_vote_1bit(FAKE_IN, 4, 100, 2, 1, pr, FAKE_OUT, None) == E
+    assert L.brace_vote_1bit(FAKE_IN, 4, 100, 0, 5, pr, FAKE_OUT, None) == E
+    assert L.brace_vote_1bit(FAKE_IN, 4, 1 << 62, 0, 1, pr, FAKE_OUT, None) == R
+    maj = B.make_params(0.0, rule=1)
+    assert L.brace_vote_1bit(FAKE_IN, 4, 100, 0, 1, ctypes.byref(maj), FAKE_OUT, None) == E
+    assert L.brace_vote_1bit(None, 4, 0, 0, 1, pr, None, None) == B.BRACE_OK
+
+
 def test_rar_aggregate_rejects_invalid_arguments(L):
     def call(inp=FAKE_IN, n=4, d=100, mean=0, ld=0, out=FAKE_OUT, size=None, chunk=None):
         p = B.BraceRarParams(ctypes.sizeof(B.BraceRarParams) if size is None else size, mean, ld)
