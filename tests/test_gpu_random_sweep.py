@@ -263,6 +263,24 @@ def test_planes_random_case(seed):
         unpacked_c = np.unpackbits(bits_c.cpu().numpy().view(np.uint8), bitorder="little")
         assert np.array_equal(unpacked_c[lo:hi], (want.out[lo:hi] > 0).astype(np.uint8)), (tag, a, b)
         assert not unpacked_c[:lo].any() and not unpacked_c[hi:].any(), (tag, a, b)
+    if zs != 0:
+        # every coordinate votes: the one-bit form must give the same vector
+        vwords = O.vote_plane_row_words(d)
+        vstore = torch.full((n, vwords + 4), -1, device=DEV, dtype=torch.int32)
+        votes = vstore[:, :vwords]
+        try:
+            B.brace_set_tuning(stage_writes=stage)
+            B.brace_quantize_1bit(upd, zs, votes)
+        finally:
+            B.brace_reset_tuning()
+        whole_v, out_v = guarded(d, 5.0, torch.float32)
+        B.brace_vote_1bit(votes, d, 0, lam, out=out_v)
+        torch.cuda.synchronize()
+        hv = vstore.cpu().numpy()
+        assert np.array_equal(hv[:, :vwords].view(np.uint32), O.vote_plane(g, zs)), tag
+        assert (hv[:, vwords:] == -1).all(), tag
+        assert np.array_equal(out_v.cpu().numpy(), want.out), tag
+        assert untouched(whole_v, d, 5.0), tag
     # receive side of Share-Only from those bits
     whole2, out2 = guarded(d, 3.0, torch.float32, 1)
     B.brace_expand_bits(bits, d, out2)
