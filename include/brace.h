@@ -207,6 +207,10 @@ int brace_quantize_1bit(const float* updates_dev, int64_t n, int64_t d, int64_t 
                         uint32_t* votes_dev, int64_t ld_words, void* hip_stream);
 int brace_vote_1bit(const uint32_t* votes_dev, int64_t n, int64_t d, int64_t ld_words, int64_t f,
                     const brace_params_t* params, float* out_dev, void* hip_stream);
+/* The run of ring chunks [chunk_begin, chunk_end) only, as brace_vote_packed_chunks. */
+int brace_vote_1bit_chunks(const uint32_t* votes_dev, int64_t n, int64_t d, int64_t ld_words,
+                           int64_t f, int64_t chunk_begin, int64_t chunk_end,
+                           const brace_params_t* params, float* out_dev, void* hip_stream);
 
 /*
  * Sec. 3 Phase III on its own, for an owner that holds partial sign-sums: in Share-Reduce

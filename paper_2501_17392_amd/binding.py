@@ -69,7 +69,7 @@ EXPORTS = (
     "brace_packed_row_words", "brace_quantize", "brace_vote_packed", "brace_vote_packed_chunk",
     "brace_vote_packed_chunks", "brace_aggregate_chunks", "brace_consensus_sums",
     "brace_set_pointer_checks", "brace_init_device", "brace_comm_cost",
-    "brace_1bit_row_words", "brace_quantize_1bit", "brace_vote_1bit",
+    "brace_1bit_row_words", "brace_quantize_1bit", "brace_vote_1bit", "brace_vote_1bit_chunks",
 )
 
 
@@ -145,6 +145,8 @@ def lib():
     L.brace_quantize_1bit.restype = ctypes.c_int
     L.brace_vote_1bit.argtypes = [vp, i64, i64, i64, i64, pp, vp, vp]
     L.brace_vote_1bit.restype = ctypes.c_int
+    L.brace_vote_1bit_chunks.argtypes = [vp, i64, i64, i64, i64, i64, i64, pp, vp, vp]
+    L.brace_vote_1bit_chunks.restype = ctypes.c_int
     rp = ctypes.POINTER(BraceRarParams)
     L.brace_rar_aggregate.argtypes = [vp, i64, i64, rp, vp, vp]
     L.brace_rar_aggregate.restype = ctypes.c_int
@@ -373,6 +375,17 @@ def brace_vote_1bit(votes, d: int, f: int, lam: float = 5.0, out=None, out_bits=
     p = make_params(lam, 0, 0, _ptr(out_bits), None)
     _check(lib().brace_vote_1bit(votes.data_ptr(), n, d, ld_words, f, ctypes.byref(p), _ptr(out),
                                  _stream_handle(stream)))
+    return out
+
+
+def brace_vote_1bit_chunks(votes, d: int, f: int, chunk_begin: int, chunk_end: int, lam: float = 5.0,
+                           out=None, out_bits=None, stream=None):
+    """brace_vote_1bit for a run of consecutive ring chunks; `out` / `out_bits` are the FULL vectors."""
+    n = votes.shape[0]
+    ld_words = votes.stride(0) if n > 1 else 0
+    p = make_params(lam, 0, 0, _ptr(out_bits), None)
+    _check(lib().brace_vote_1bit_chunks(votes.data_ptr(), n, d, ld_words, f, chunk_begin, chunk_end,
+                                        ctypes.byref(p), _ptr(out), _stream_handle(stream)))
     return out
 
 

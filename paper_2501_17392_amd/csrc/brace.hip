@@ -284,6 +284,39 @@ __global__ void brace_clear_pad_kernel(uint32_t* bits, int64_t d)
         atomicAnd(&bits[d >> 5], (1u << (d & 31)) - 1u);
 }
 
+// The same for one-bit votes: S = 2P - n with P the number of set bits among the n clients.
+__global__ void __launch_bounds__(kBlock)
+brace_1bit_edge_kernel(const uint32_t* __restrict__ votes, int64_t ld_words, int n, int thresh,
+                       float* out, uint32_t* bits, int64_t lo, int64_t lo_a, int64_t hi_a,
+                       int64_t hi, int64_t hi_ext)
+{
+    const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int64_t head = lo_a - lo;
+    const int64_t k = (e < head) ? lo + e : hi_a + (e - head);
+    if (k >= hi_ext)
+        return;
+    const uint32_t bit = 1u << (k & 31);
+    if (k >= hi) {
+        atomicAnd(&bits[k >> 5], ~bit);
+        return;
+    }
+    const uint32_t* word = votes + (k >> 5);
+    int up_votes = 0;
+    for (int i = 0; i < n; ++i) {
+        up_votes += (*word & bit) ? 1 : 0;
+        word += ld_words;
+    }
+    const bool up = 2 * up_votes - n >= thresh;
+    if (out)
+        out[k] = up ? 1.0f : -1.0f;
+    if (bits) {
+        if (up)
+            atomicOr(&bits[k >> 5], bit);
+        else
+            atomicAnd(&bits[k >> 5], ~bit);
+    }
+}
+
 // ---------------------------------------------------------------------------------------
 // Measurement aids: a plain streaming read and a plain copy of a buffer of known size.
 // They calibrate what the HBM counters report per byte and give the bandwidth a trivially
@@ -1416,8 +1449,10 @@ int brace_quantize_1bit(const float* updates_dev, int64_t n, int64_t d, int64_t 
     return check_launch("one-bit quantize kernel");
 }
 
-int brace_vote_1bit(const uint32_t* votes_dev, int64_t n, int64_t d, int64_t ld_words, int64_t f,
-                    const brace_params_t* params, float* out_dev, void* hip_stream)
+// Phases II-IV on one-bit votes over the coordinate range [lo, hi).
+static int onebit_range(const uint32_t* votes_dev, int64_t n, int64_t d, int64_t ld_words, int64_t f,
+                        const brace_params_t* params, float* out_dev, int64_t lo, int64_t hi,
+                        hipStream_t stream)
 {
     if (!params)
         return fail(BRACE_EINVAL, "params is NULL");
@@ -1441,7 +1476,7 @@ int brace_vote_1bit(const uint32_t* votes_dev, int64_t n, int64_t d, int64_t ld_
         return fail(BRACE_EINVAL, "ld_words must be a multiple of 4 and >= brace_1bit_row_words(d)");
     if (check_extent(n, ld_words, 4) != BRACE_OK)
         return BRACE_ERANGE;
-    if (d == 0)
+    if (d == 0 || hi <= lo)
         return BRACE_OK;
     uint32_t* bits = static_cast<uint32_t*>(params->out_bits_dev);
     if (!votes_dev || !aligned_to(votes_dev, 16))
@@ -1472,28 +1507,83 @@ int brace_vote_1bit(const uint32_t* votes_dev, int64_t n, int64_t d, int64_t ld_
         rc = check_device_range(bits, ((d + 31) / 32) * 4, "out_bits_dev");
     if (rc != BRACE_OK)
         return rc;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const int64_t cols4 = row_words / 4;
-    const int64_t grid = (cols4 + kBlock - 1) / kBlock;
-    if (grid > 0x7fffffffLL)
-        return fail(BRACE_ERANGE, "vector too long for one launch");
-    uint32_t* dst = bits ? bits : reinterpret_cast<uint32_t*>(out_dev);
-    const int scratch = bits ? 0 : 1;
-    const u32x4* planes = reinterpret_cast<const u32x4*>(votes_dev);
-    if (n <= 255)
-        hipLaunchKernelGGL(brace_vote_1bit_kernel<8>, dim3((unsigned)grid), dim3(kBlock), 0, stream,
-                           planes, ld_words / 4, ni, cols4, q, dst, scratch, d);
-    else
-        hipLaunchKernelGGL(brace_vote_1bit_kernel<16>, dim3((unsigned)grid), dim3(kBlock), 0, stream,
-                           planes, ld_words / 4, ni, cols4, q, dst, scratch, d);
-    rc = check_launch("one-bit vote kernel");
-    if (rc != BRACE_OK || !out_dev)
-        return rc;
-    const int64_t groups = (d + kGroup - 1) / kGroup;
-    const int64_t egrid = (groups + kWaves - 1) / kWaves;
-    hipLaunchKernelGGL(brace_expand_kernel, dim3((unsigned)egrid), dim3(kBlock), 0, stream, out_dev,
-                       static_cast<const uint32_t*>(bits), (int64_t)0, groups, d);
-    return check_launch("expand kernel");
+    // Whole vector: the slice kernel covers everything, ragged end included.  A sub-range is
+    // split like the two-plane vote: whole 1024-coordinate groups through the slice kernel on
+    // offset pointers, the coordinates before and after them one per thread.
+    const bool whole = lo == 0 && hi == d;
+    int64_t lo_a = whole ? 0 : (lo + kGroup - 1) / kGroup * kGroup;
+    int64_t hi_a = whole ? d : hi / kGroup * kGroup;
+    if (lo_a >= hi_a)
+        lo_a = hi_a = lo;          // no body: the whole range is edge
+    if (hi_a > lo_a) {
+        const int64_t d_body = hi_a - lo_a;
+        const int64_t cols4 = whole ? row_words / 4 : d_body / 128;
+        const int64_t grid = (cols4 + kBlock - 1) / kBlock;
+        if (grid > 0x7fffffffLL)
+            return fail(BRACE_ERANGE, "vector too long for one launch");
+        uint32_t* dst = bits ? bits + lo_a / 32 : reinterpret_cast<uint32_t*>(out_dev + lo_a);
+        const int scratch = bits ? 0 : 1;
+        const u32x4* planes = reinterpret_cast<const u32x4*>(votes_dev + lo_a / 32);
+        if (n <= 255)
+            hipLaunchKernelGGL(brace_vote_1bit_kernel<8>, dim3((unsigned)grid), dim3(kBlock), 0,
+                               stream, planes, ld_words / 4, ni, cols4, q, dst, scratch, d_body);
+        else
+            hipLaunchKernelGGL(brace_vote_1bit_kernel<16>, dim3((unsigned)grid), dim3(kBlock), 0,
+                               stream, planes, ld_words / 4, ni, cols4, q, dst, scratch, d_body);
+        rc = check_launch("one-bit vote kernel");
+        if (rc != BRACE_OK)
+            return rc;
+        if (out_dev) {
+            const int64_t groups = (d_body + kGroup - 1) / kGroup;
+            const int64_t egrid = (groups + kWaves - 1) / kWaves;
+            hipLaunchKernelGGL(brace_expand_kernel, dim3((unsigned)egrid), dim3(kBlock), 0, stream,
+                               out_dev, static_cast<const uint32_t*>(bits), lo_a, groups, hi_a);
+            rc = check_launch("expand kernel");
+            if (rc != BRACE_OK)
+                return rc;
+        }
+    }
+    if (whole)
+        return BRACE_OK;
+    int64_t hi_ext = hi;
+    if (bits && hi == d)
+        hi_ext = (d + 31) & ~(int64_t)31;          // the last word's padding bits are zeroed
+    const int64_t edge = (lo_a - lo) + (hi_ext - hi_a);
+    if (edge > 0) {
+        const int64_t tgrid = (edge + kBlock - 1) / kBlock;
+        hipLaunchKernelGGL(brace_1bit_edge_kernel, dim3((unsigned)tgrid), dim3(kBlock), 0, stream,
+                           votes_dev, ld_words, ni, thresh, out_dev, bits, lo, lo_a, hi_a, hi, hi_ext);
+        rc = check_launch("one-bit edge kernel");
+    }
+    return rc;
+}
+
+int brace_vote_1bit(const uint32_t* votes_dev, int64_t n, int64_t d, int64_t ld_words, int64_t f,
+                    const brace_params_t* params, float* out_dev, void* hip_stream)
+{
+    return onebit_range(votes_dev, n, d, ld_words, f, params, out_dev, 0, d < 0 ? 0 : d,
+                        static_cast<hipStream_t>(hip_stream));
+}
+
+int brace_vote_1bit_chunks(const uint32_t* votes_dev, int64_t n, int64_t d, int64_t ld_words,
+                           int64_t f, int64_t chunk_begin, int64_t chunk_end,
+                           const brace_params_t* params, float* out_dev, void* hip_stream)
+{
+    if (n < 1 || d < 0)
+        return fail(BRACE_EINVAL, "need n >= 1 and d >= 0");
+    if (chunk_begin < 0 || chunk_end > n || chunk_begin > chunk_end)
+        return fail(BRACE_ERANGE, "chunk range [%lld, %lld) outside [0, %lld]",
+                    (long long)chunk_begin, (long long)chunk_end, (long long)n);
+    int64_t lo = 0, hi = 0, unused;
+    if (chunk_begin < chunk_end) {
+        int rc = brace_chunk_range(n, d, chunk_begin, &lo, &unused);
+        if (rc == BRACE_OK)
+            rc = brace_chunk_range(n, d, chunk_end - 1, &unused, &hi);
+        if (rc != BRACE_OK)
+            return rc;
+    }
+    return onebit_range(votes_dev, n, d, ld_words, f, params, out_dev, lo, hi,
+                        static_cast<hipStream_t>(hip_stream));
 }
 
 int brace_consensus_sums(const int16_t* parts_dev, int64_t g, int64_t d, int64_t ld,

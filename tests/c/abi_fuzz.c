@@ -52,7 +52,7 @@ int main(void)
         const int64_t f = n > 0 ? (int64_t)(rnd() % (uint64_t)(n + 1)) : 0;
         const int64_t c = n > 0 ? (int64_t)(rnd() % (uint64_t)(n + 2)) - 1 : 0;
         int rc;
-        switch (rnd() % 14) {
+        switch (rnd() % 15) {
         case 0: rc = brace_aggregate(in, n, d, f, &p, out, NULL); break;
         case 1: rc = brace_aggregate_chunk(in, n, d, f, c, &p, out, NULL); break;
         case 2: rc = brace_aggregate_chunks(in, n, d, f, c, c + (int64_t)(rnd() % 5), &p, out, NULL); break;
@@ -75,6 +75,9 @@ int main(void)
                                           (rnd() % 2) ? 0 : brace_1bit_row_words(d) + 4 * (int64_t)(rnd() % 3), NULL); break;
         case 13: p.sums_dev = NULL; p.rule = 0;
                  rc = brace_vote_1bit((const uint32_t*)base_in, n, d, 0, f, &p, out ? (float*)base_out : NULL, NULL); break;
+        case 14: p.sums_dev = NULL; p.rule = 0;
+                 rc = brace_vote_1bit_chunks((const uint32_t*)base_in, n, d, 0, f, c, c + (int64_t)(rnd() % 5), &p,
+                                             out ? (float*)base_out : NULL, NULL); break;
         case 10: rc = brace_expand_bits((const void*)base_aux, d, out, NULL); break;
         default: rc = brace_apply_bits((const void*)base_aux, d, 0.01f, out, NULL); break;
         }

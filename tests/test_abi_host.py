@@ -350,6 +350,10 @@ def test_one_bit_entry_points_validate(L):
     maj = B.make_params(0.0, rule=1)
     assert L.brace_vote_1bit(FAKE_IN, 4, 100, 0, 1, ctypes.byref(maj), FAKE_OUT, None) == E
     assert L.brace_vote_1bit(None, 4, 0, 0, 1, pr, None, None) == B.BRACE_OK
+    assert L.brace_vote_1bit_chunks(FAKE_IN, 4, 100, 0, 1, 2, 1, pr, FAKE_OUT, None) == R
+    assert L.brace_vote_1bit_chunks(FAKE_IN, 4, 100, 0, 1, 0, 5, pr, FAKE_OUT, None) == R
+    assert L.brace_vote_1bit_chunks(None, 4, 100, 0, 1, 0, 2, pr, FAKE_OUT, None) == E
+    assert L.brace_vote_1bit_chunks(None, 4, 100, 0, 1, 2, 2, pr, None, None) == B.BRACE_OK
 
 
 def test_rar_aggregate_rejects_invalid_arguments(L):

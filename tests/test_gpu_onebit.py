@@ -116,6 +116,35 @@ def test_one_bit_vote_output_variants(d):
     assert np.array_equal(bits.cpu().numpy().view(np.uint8)[: (d + 7) // 8], want.bits)
 
 
+@pytest.mark.parametrize("n,d", [(3, 3), (7, 3), (5, 1024), (10, 10_000), (20, 100_003), (13, 4096),
+                                 (6, 70_001), (37, 300_007), (100, 250_000)])
+def test_one_bit_chunk_runs_tile_the_whole(n, d):
+    g = special(n, d, seed=n + d)
+    upd = to_device(g)
+    for zs, lam in ((1, 1.0), (-1, -2.0)):
+        votes = torch.empty(n, B.brace_1bit_row_words(d), device=DEV, dtype=torch.int32)
+        B.brace_quantize_1bit(upd, zs, votes)
+        want = O.brace_direct(g, lam, zs)
+        out = torch.full((d,), 7.0, device=DEV, dtype=torch.float32)
+        bits = torch.zeros((d + 31) // 32, device=DEV, dtype=torch.int32)
+        for c in np.random.default_rng(n).permutation(n):       # chunk by chunk, scrambled
+            B.brace_vote_1bit_chunks(votes, d, 0, int(c), int(c) + 1, lam, out=out, out_bits=bits)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), want.out), (n, d, zs)
+        got_bits = bits.cpu().numpy().view(np.uint8)
+        assert np.array_equal(got_bits[: (d + 7) // 8], want.bits)
+        assert not got_bits[(d + 7) // 8:].any()
+        guard = torch.full((d + 128,), 7.0, device=DEV, dtype=torch.float32)
+        out2 = guard[64: 64 + d]
+        a, b = n // 3, max(n // 3 + 1, (2 * n) // 3)            # one run in the middle, floats only
+        B.brace_vote_1bit_chunks(votes, d, 0, a, b, lam, out=out2)
+        torch.cuda.synchronize()
+        lo, hi = O.chunk_range(n, d, a)[0], O.chunk_range(n, d, b - 1)[1]
+        h = guard.cpu().numpy()
+        assert np.array_equal(h[64 + lo: 64 + hi], want.out[lo:hi])
+        assert (h[: 64 + lo] == 7.0).all() and (h[64 + hi:] == 7.0).all()
+
+
 @pytest.mark.parametrize("idx,col_tile", [(2, 2_000_000), (3, 2_000_000), (4, 4_000_000)])
 def test_one_bit_large_workloads_full(idx, col_tile):
     w = synth.WORKLOADS[idx]
