@@ -745,10 +745,7 @@ int launch_vote(const float* updates, int64_t n, int64_t d, int64_t ld, int thre
 
     const int64_t slots = (a.hi_a - a.lo_a) / (64 * (int64_t)v);
     const bool plain_floats = !split && !bits && !p->sums_dev && (out || w);
-    // The in-place update moves 8 bytes per coordinate; below 16 clients that is so large a
-    // share of the traffic that the burst's read-modify-write stalls more than it saves
-    // (n = 8, d = 100 M: 666 us with stores per wave, 727 us staged; n = 16: 604 / 591).
-    const bool stage_ok = plain_floats && (!w || n >= kStageBelowClients || t.stage_writes == 2);
+    const bool stage_ok = plain_floats;
     // Sign-sums alone (the partial sums a device contributes to Share-Reduce) are staged the
     // same way (n = 12, d = 100 M: 852 us with stores per wave, 727 us for the reads alone).
     const bool sums_only = p->sums_dev && !out && !w && !bits;

@@ -142,12 +142,23 @@ struct VoteOp {
             atomicAnd(&bits[k >> 5], ~(1u << (k & 31)));
     }
 
-    // Staged variant: the float result and / or the in-place model update, or (stage_sums)
-    // the sign-sums alone -- the partial sums of Share-Reduce, exact in a float up to 2^24.
-    __device__ __forceinline__ float stage_value(const State& st, int n) const
+    // Staged variant: the float result, the in-place model update, or (stage_sums) the
+    // sign-sums alone -- the partial sums of Share-Reduce, exact in a float up to 2^24.
+    // For the update the old parameters of a tile are requested before its rows, so that
+    // they arrive under the row stream and the burst at the end is write-only.
+    template <int V>
+    __device__ __forceinline__ typename Vec<V>::type stage_prefetch(int64_t k) const
+    {
+        typename Vec<V>::type zero = {};
+        return w ? load_vec<V, true>(w + k) : zero;
+    }
+
+    __device__ __forceinline__ float stage_value(const State& st, int n, float old) const
     {
         const int s = sign_sum(st, n);
-        return stage_sums ? (float)s : decide(s);
+        if (stage_sums)
+            return (float)s;
+        return w ? old - eta * decide(s) : decide(s);
     }
 
     __device__ __forceinline__ void flush4(int64_t k, f32x4 v) const
@@ -160,13 +171,7 @@ struct VoteOp {
             __builtin_nontemporal_store(s4, reinterpret_cast<typename IVec<4>::type*>(sums + k));
             return;
         }
-        if (out)
-            __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(out + k));
-        if (w) {
-            f32x4 wv = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(w + k));
-            wv -= eta * v;
-            __builtin_nontemporal_store(wv, reinterpret_cast<f32x4*>(w + k));
-        }
+        __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(w ? w + k : out + k));
     }
 };
 
@@ -200,7 +205,14 @@ struct SumOp {
 
     __device__ __forceinline__ void pad_edge(int64_t) const {}
 
-    __device__ __forceinline__ float stage_value(const State& st, int) const
+    template <int V>
+    __device__ __forceinline__ typename Vec<V>::type stage_prefetch(int64_t) const
+    {
+        typename Vec<V>::type zero = {};
+        return zero;
+    }
+
+    __device__ __forceinline__ float stage_value(const State& st, int, float) const
     {
         return (float)(st.acc * scale);
     }

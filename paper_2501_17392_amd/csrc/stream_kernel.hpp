@@ -33,7 +33,11 @@
 //   void store_edge(int64_t k, const State&, int n) const;     one coordinate
 //   void pad_edge(int64_t k) const;                coordinate in [hi, hi_ext): op-specific padding
 // and, for the staged variant (one float per coordinate, written in large bursts):
-//   float stage_value(const State&, int n) const;  the float a coordinate ends up as
+//   template <int V> Vec<V>::type stage_prefetch(int64_t k) const;
+//                                                  what the op wants to have read before the
+//                                                  rows of a tile (old values it updates)
+//   float stage_value(const State&, int n, float old) const;
+//                                                  the float a coordinate ends up as
 //   void flush4(int64_t k, f32x4 v) const;         consume 4 consecutive coordinates from k
 
 #pragma once
@@ -327,21 +331,29 @@ stream_staged_kernel(const float* __restrict__ updates, const StreamArgs a, cons
             break;                                              // wave-uniform; the barrier is below
         if (s0 + COLS <= slots) {
             State st[COLS][V];
+            typename Vec<V>::type old[COLS];
+#pragma unroll
+            for (int c = 0; c < COLS; ++c)
+                old[c] = op.template stage_prefetch<V>(a.lo_a + (s0 + c) * kSlot + lane * V);
             stream_accumulate<Op, V, COLS, RU, true, PIPE>(updates, a.ld, a.n, a.lo_a + s0 * kSlot,
                                                            lane, st);
 #pragma unroll
             for (int c = 0; c < COLS; ++c)
 #pragma unroll
                 for (int e = 0; e < V; ++e)
-                    stage[(s0 - slot0 + c) * kSlot + lane * V + e] = op.stage_value(st[c][e], a.n);
+                    stage[(s0 - slot0 + c) * kSlot + lane * V + e] =
+                        op.stage_value(st[c][e], a.n, elem<V>(old[c], e));
         } else {
             for (int64_t s = s0; s < slots; ++s) {              // ragged end of the range
                 State st[1][V];
+                const typename Vec<V>::type old =
+                    op.template stage_prefetch<V>(a.lo_a + s * kSlot + lane * V);
                 stream_accumulate<Op, V, 1, RU, true, PIPE>(updates, a.ld, a.n, a.lo_a + s * kSlot,
                                                             lane, st);
 #pragma unroll
                 for (int e = 0; e < V; ++e)
-                    stage[(s - slot0) * kSlot + lane * V + e] = op.stage_value(st[0][e], a.n);
+                    stage[(s - slot0) * kSlot + lane * V + e] =
+                        op.stage_value(st[0][e], a.n, elem<V>(old, e));
             }
         }
     }
