@@ -264,8 +264,9 @@ int brace_init_device(void);
 const char* brace_last_error(void);
 
 /*
- * Launch tuning for the streaming kernel (process-wide, not thread-safe; meant for
- * benchmarks and autotuning).  Every combination produces identical results.
+ * Launch tuning for the streaming kernel (process-wide: a call reads the setting in force when
+ * it is made; meant for benchmarks and autotuning).  Every combination produces identical
+ * results.
  */
 typedef struct brace_tuning {
     uint32_t struct_size;  /* sizeof(brace_tuning_t)                                             */

@@ -9,7 +9,9 @@
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
+#include <atomic>
 #include <cstring>
+#include <mutex>
 
 #include "brace.h"
 #include "ops.hpp"
@@ -62,24 +64,40 @@ constexpr int kMaxDevices = 64;            // per-device caches; devices beyond 
 // Compute units of the current device (0 if it cannot be queried); cached per device.
 int compute_units()
 {
-    static int cached[kMaxDevices] = {};   // 0 = not known yet
+    static std::atomic<int> cached[kMaxDevices];   // zero-initialised: 0 = not known yet
     int dev = 0, cu = 0;
     if (hipGetDevice(&dev) != hipSuccess) {
         (void)hipGetLastError();
         return 0;
     }
-    if (dev >= 0 && dev < kMaxDevices && cached[dev] > 0)
-        return cached[dev];
+    if (dev >= 0 && dev < kMaxDevices) {
+        const int known = cached[dev].load(std::memory_order_relaxed);
+        if (known > 0)
+            return known;
+    }
     if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) {
         (void)hipGetLastError();
         return 0;
     }
     if (dev >= 0 && dev < kMaxDevices)
-        cached[dev] = cu;
+        cached[dev].store(cu, std::memory_order_relaxed);
     return cu;
 }
 
 brace_tuning_t g_tuning = default_tuning();
+std::mutex g_tuning_guard;
+
+brace_tuning_t current_tuning()
+{
+    const std::lock_guard<std::mutex> lock(g_tuning_guard);
+    return g_tuning;
+}
+
+void store_tuning(const brace_tuning_t& t)
+{
+    const std::lock_guard<std::mutex> lock(g_tuning_guard);
+    g_tuning = t;
+}
 
 // Second phase of a split call: one wave turns the 32 bit-words of a 1024-coordinate group
 // into 1024 floats.  `words` is the linear bit array, or null when the words were parked in
@@ -546,7 +564,7 @@ int64_t plan_range(StreamArgs& a, Shape& shape, const brace_tuning_t& t, int64_t
 // will touch must lie inside the allocation that holds the pointer.  A wrong shape is then
 // an error code on the host instead of a memory fault on the device.  Can be switched off
 // (brace_set_pointer_checks) by callers that cannot afford the two runtime queries per buffer.
-bool g_pointer_checks = true;
+std::atomic<bool> g_pointer_checks{true};
 
 int check_device_range(const void* ptr, int64_t bytes, const char* name)
 {
@@ -647,6 +665,8 @@ int allow_stage_lds(const void* kernel)
 {
     struct Seen { const void* kernel; int dev; };
     static Seen done[64] = {};
+    static std::mutex guard;                   // entry points may be called from several threads
+    const std::lock_guard<std::mutex> lock(guard);
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) {
         (void)hipGetLastError();
@@ -688,7 +708,7 @@ int launch_vote(const float* updates, int64_t n, int64_t d, int64_t ld, int thre
     int rc = check_buffers(updates, n, d, ld, out, p->out_bits_dev, p->sums_dev, w);
     if (rc != BRACE_OK)
         return rc;
-    const brace_tuning_t t = g_tuning;
+    const brace_tuning_t t = current_tuning();
     int v = pick_width(updates, n, ld, out, p->sums_dev, t.vec);
     if (w)
         v = pick_width(updates, n, ld, w, nullptr, v);
@@ -807,7 +827,7 @@ int launch_sum(const float* updates, int64_t n, int64_t d, int64_t ld, double sc
     const int rc = check_buffers(updates, n, d, ld, out, nullptr, nullptr, nullptr);
     if (rc != BRACE_OK)
         return rc;
-    const brace_tuning_t t = g_tuning;
+    const brace_tuning_t t = current_tuning();
     const int v = pick_width(updates, n, ld, out, nullptr, t.vec);
     SumOp op;
     op.out = out;
@@ -1158,7 +1178,7 @@ int brace_quantize(const float* updates_dev, int64_t n, int64_t d, int64_t ld,
         return rc;
     const int64_t spans = (d + kQuantSpan - 1) / kQuantSpan;
     const int64_t groups = (spans + kQuantGroup - 1) / kQuantGroup;    // per row
-    const brace_tuning_t t = g_tuning;
+    const brace_tuning_t t = current_tuning();
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     // The burst kernel runs one block per compute unit at a time (2 MiB of input each), so its
     // blocks come in rounds and a thinly filled last round costs as much as a full one.
@@ -1414,7 +1434,7 @@ int brace_quantize_1bit(const float* updates_dev, int64_t n, int64_t d, int64_t 
         return rc;
     const int64_t spans = (d + kQuantSpan - 1) / kQuantSpan;
     const int64_t groups = (spans + kVoteGroup - 1) / kVoteGroup;       // per row
-    const brace_tuning_t t = g_tuning;
+    const brace_tuning_t t = current_tuning();
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int up = zero_sign == 1 ? 1 : 0;
     // Same rule as the two-plane kernel: bursts when the blocks come in well filled rounds.
@@ -1704,7 +1724,7 @@ const char* brace_last_error(void)
 int brace_set_tuning(const brace_tuning_t* tuning)
 {
     if (!tuning) {
-        g_tuning = default_tuning();
+        store_tuning(default_tuning());
         return BRACE_OK;
     }
     if (tuning->struct_size != sizeof(brace_tuning_t))
@@ -1717,7 +1737,7 @@ int brace_set_tuning(const brace_tuning_t* tuning)
         tuning->rowsplit > 2 || tuning->stage_writes < 0 || tuning->stage_writes > 2)
         return fail(BRACE_EINVAL, "tuning: vec in {0,1,2,4}, cols in {0,1,2,4,8}, unroll in {0,2,4,8}, "
                     "split_writes, rowsplit and stage_writes in {0,1,2}");
-    g_tuning = *tuning;
+    store_tuning(*tuning);
     return BRACE_OK;
 }
 
@@ -1725,7 +1745,7 @@ int brace_get_tuning(brace_tuning_t* tuning)
 {
     if (!tuning)
         return fail(BRACE_EINVAL, "tuning is NULL");
-    *tuning = g_tuning;
+    *tuning = current_tuning();
     return BRACE_OK;
 }
 
