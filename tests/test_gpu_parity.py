@@ -478,3 +478,46 @@ def test_wrong_buffers_are_rejected_on_the_host():
         assert (good == 1.0).all()
     finally:
         B.brace_set_pointer_checks(True)
+
+
+def test_calls_from_several_host_threads():
+    """Four host threads, each with its own stream, inputs and outputs, call the entry points
+    at the same time (ctypes releases the interpreter lock during a call); every result must
+    match the oracle and an error on one thread must not leak its text to another."""
+    import threading
+    n, d = 9, 120_003
+    inputs = [special_matrix(n, d, seed=500 + t) for t in range(4)]
+    wants = [O.brace_direct(v.cpu().numpy(), 1.0) for v in inputs]
+    sums_ref = [O.rar_sum_direct(np.nan_to_num(v.cpu().numpy(), nan=0.0, posinf=0.0, neginf=0.0))
+                for v in inputs]
+    clean = [torch.nan_to_num(v, nan=0.0, posinf=0.0, neginf=0.0).contiguous() for v in inputs]
+    failures = []
+
+    def worker(t):
+        try:
+            stream = torch.cuda.Stream()
+            out = torch.empty(d, device=DEV, dtype=torch.float32)
+            total = torch.empty(d, device=DEV, dtype=torch.float32)
+            bits = torch.empty((d + 31) // 32, device=DEV, dtype=torch.int32)
+            for it in range(25):
+                B.brace_aggregate(inputs[t], 0, 1.0, out=out, out_bits=bits, stream=stream)
+                B.brace_rar_aggregate(clean[t], total, stream=stream)
+                if it % 5 == t % 5:
+                    with pytest.raises(B.BraceError) as err:     # an error of this thread's own
+                        B.brace_aggregate_chunk(inputs[t], 0, n + t, 1.0, out=out, stream=stream)
+                    assert f"chunk {n + t} " in str(err.value)
+            stream.synchronize()
+            assert np.array_equal(out.cpu().numpy(), wants[t].out)
+            assert np.array_equal(bits.cpu().numpy().view(np.uint8)[: (d + 7) // 8], wants[t].bits)
+            got = total.cpu().numpy().astype(np.float64)
+            assert np.all(np.abs(got - sums_ref[t]) <= 1e-6 + 1e-5 * np.abs(sums_ref[t]))
+        except BaseException as e:                               # reported by the main thread
+            failures.append((t, repr(e)))
+
+    threads = [threading.Thread(target=worker, args=(t,)) for t in range(4)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    torch.cuda.synchronize()
+    assert not failures, failures
