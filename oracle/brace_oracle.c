@@ -111,3 +111,33 @@ int oracle_rar_sum(const float *updates, int64_t n, int64_t d, int64_t ld,
     }
     return 0;
 }
+
+/*
+ * Plain RAR as a ring of fp32 clients delivers it (Sec. 2.2, Share-Reduce): chunk c starts
+ * as client c's sub-vector and every following client on the ring adds its own, so
+ * coordinate k of chunk c is ((g_c + g_{c+1}) + ...) + g_{c-1} (indices mod n), each +
+ * rounded to float.  Chunks: the first d mod n hold one coordinate more.  With mean != 0
+ * the sum is divided by n once, in float (Mean rule of Sec. 2.1).
+ */
+int oracle_rar_sum_ring_f32(const float *updates, int64_t n, int64_t d, int64_t ld,
+                            int mean, float *out, int threads)
+{
+    if (!updates || !out || n < 1 || d < 0 || ld < d)
+        return -1;
+    const int64_t q = d / n, r = d % n;
+#ifdef _OPENMP
+    int nt = oracle_threads(threads);
+#pragma omp parallel for num_threads(nt) schedule(static)
+#endif
+    for (int64_t k = 0; k < d; ++k) {
+        /* chunk of k: the first r chunks have q + 1 coordinates */
+        int64_t c = (k < r * (q + 1)) ? k / (q + 1) : r + (k - r * (q + 1)) / q;
+        volatile float acc = updates[c * ld + k];      /* volatile: one rounding per step */
+        for (int64_t s = 1; s < n; ++s)
+            acc = acc + updates[((c + s) % n) * ld + k];
+        if (mean)
+            acc = acc / (float)n;
+        out[k] = acc;
+    }
+    return 0;
+}

@@ -19,6 +19,8 @@ What follows the paper, and where:
 * chunk partition .............. Sec. 2.2 (n sub-vectors of about equal size)
 * communication cost ........... Sec. 2.1 (SC), Sec. 2.2 (RAR), Sec. 3 / Table 1
 * Mean rule, model update ...... Sec. 2.1; Sec. 2.2; App. A (update rule)
+* ring-order float sum ......... Sec. 2.2 Share-Reduce (the receiver adds its own
+                                 sub-vector), in the clients' own precision
 
 Readings taken where the paper is silent (each is switchable or checked by a
 test, none is pinned by a printed value):
@@ -31,6 +33,10 @@ test, none is pinned by a printed value):
                                                          [parity unpinned]
 * one-bit form (vote_plane): bit = 1 where the vote is +1, LSB first, rows padded
   to 16 bytes; same status as the two-plane layout below.   [parity unpinned]
+* precision of the plain ring sum: the paper counts m bits per dimension and never
+  names a floating format; reading: the clients hold fp32 (m = 32, as in the traffic
+  example of Sec. 3) and add in it.  The ORDER of the additions is pinned by the
+  three-client example; the format is this build's reading.
 * bit planes of the quantise-once form (sign_planes): per client, word pair j
   = ("x > 0" bits, "x < 0" bits) of coordinates 32j .. 32j+31, LSB first, rows
   padded to an even number of pairs.  A storage convention of this build, not
@@ -201,10 +207,15 @@ class RingResult:
 
 def ring_all_reduce(updates: np.ndarray, mode: str = "brace", lam: float = 0.0,
                     zero_sign: int = 0, m_bits: int = 32,
-                    record: bool = False) -> RingResult:
+                    record: bool = False, dtype=np.float64) -> RingResult:
     """Run the n-client ring exactly as the text describes it.
 
-    mode "sum":   plain RAR (Sec. 2.2) -- float64 addition, no quantisation.
+    mode "sum":   plain RAR (Sec. 2.2) -- floating addition, no quantisation.  `dtype` is the
+                  precision the clients hold and add their sub-vectors in: float64 gives the
+                  mathematical sum up to double rounding, float32 what a ring of clients with
+                  m = 32-bit gradients delivers (Sec. 2.2 lets every receiver add the incoming
+                  sub-vector to its own, so chunk c is accumulated in the order
+                  c, c+1, ..., c-1 (mod n), one rounding per step).
     mode "brace": Phase I sign, Phase II integer addition of signs, Phase III
                   Eq. (1) on the owned chunk, Phase IV circulate the result.
 
@@ -224,7 +235,7 @@ def ring_all_reduce(updates: np.ndarray, mode: str = "brace", lam: float = 0.0,
     if mode == "brace":
         buf = [sign_quantize(updates[i], zero_sign) for i in range(n)]   # Phase I
     else:
-        buf = [updates[i].astype(np.float64) for i in range(n)]
+        buf = [updates[i].astype(dtype) for i in range(n)]
     sent = [0] * n
     log = []
 
@@ -300,6 +311,34 @@ def cost_brace(m: int, n: int, d: int) -> Fraction:
 def rar_sum_direct(updates: np.ndarray) -> np.ndarray:
     """sum_i g_i in float64 (what plain RAR delivers to every client, Sec. 2.2)."""
     return np.asarray(updates, dtype=np.float64).sum(axis=0)
+
+
+def rar_sum_ring_order(updates: np.ndarray, dtype=np.float32) -> np.ndarray:
+    """What plain RAR delivers when the clients add in `dtype` (Sec. 2.2, Share-Reduce).
+
+    Chunk c starts as client c's own sub-vector; in step s the next client on the ring adds
+    its own sub-vector to what it received.  So coordinate k of chunk c ends as
+        (((g_c[k] + g_{c+1}[k]) + g_{c+2}[k]) + ...) + g_{c-1}[k]      (indices mod n),
+    every + rounded to `dtype`.  This is the same arithmetic as ring_all_reduce(mode="sum",
+    dtype=dtype), written per chunk instead of per message.
+    """
+    updates = np.asarray(updates)
+    n, d = updates.shape
+    out = np.zeros(d, dtype=dtype)
+    for c in range(n):
+        lo, hi = chunk_range(n, d, c)
+        acc = updates[c, lo:hi].astype(dtype)
+        for step in range(1, n):
+            acc = (acc + updates[(c + step) % n, lo:hi].astype(dtype)).astype(dtype)
+        out[lo:hi] = acc
+    return out
+
+
+def mean_ring_order(updates: np.ndarray, dtype=np.float32) -> np.ndarray:
+    """The Mean rule of Sec. 2.1 on top of the ring-order sum: one division by n in `dtype`."""
+    updates = np.asarray(updates)
+    total = rar_sum_ring_order(updates, dtype)
+    return (total / dtype(updates.shape[0])).astype(dtype)
 
 
 def mean_direct(updates: np.ndarray) -> np.ndarray:

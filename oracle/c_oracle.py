@@ -47,6 +47,9 @@ def load():
         f32p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_double,
         ctypes.POINTER(ctypes.c_double), ctypes.c_int]
     lib.oracle_rar_sum.restype = ctypes.c_int
+    lib.oracle_rar_sum_ring_f32.argtypes = [
+        f32p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, f32p, ctypes.c_int]
+    lib.oracle_rar_sum_ring_f32.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -100,4 +103,17 @@ def rar_sum(updates: np.ndarray, scale: float = 1.0, nthreads: int = 0) -> np.nd
         float(scale), out.ctypes.data_as(ctypes.POINTER(ctypes.c_double)), int(nthreads))
     if rc != 0:
         raise ValueError("oracle_rar_sum rejected its arguments")
+    return out
+
+
+def rar_sum_ring_f32(updates: np.ndarray, mean: bool = False, nthreads: int = 0) -> np.ndarray:
+    """Ring-order fp32 sum (or mean) of the client rows through the C oracle."""
+    lib = load()
+    n, d, ld = _rows(updates)
+    out = np.empty(d, dtype=np.float32)
+    rc = lib.oracle_rar_sum_ring_f32(
+        updates.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), n, d, ld, 1 if mean else 0,
+        out.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), int(nthreads))
+    if rc != 0:
+        raise ValueError("oracle_rar_sum_ring_f32 rejected its arguments")
     return out

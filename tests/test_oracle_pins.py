@@ -333,6 +333,91 @@ def test_ring_sum_equals_direct_sum():
     np.testing.assert_allclose(C.rar_sum(G, 1.0 / 6), O.mean_direct(G), rtol=1e-14, atol=1e-14)
 
 
+# --- the ring sum in the clients' own precision (Sec. 2.2 Share-Reduce) -------------------
+
+def test_fp32_ring_reproduces_the_printed_example(golden_dir):
+    # Small integers are exact in fp32: the printed steps and sums must come out unchanged.
+    ex = _golden(golden_dir, "rar_three_client_example.json")
+    G = np.array(ex["gradients"], dtype=np.float32)
+    res = O.ring_all_reduce(G, mode="sum", record=True, dtype=np.float32)
+    fw = ex["client1_forwards"]
+    hits = [m for m in res.messages if m.phase == "share_reduce" and m.step == 2 and m.src == 0]
+    assert hits[0].payload.dtype == np.float32 and hits[0].payload.tolist() == [fw["value"]]
+    for b in res.buffers:
+        assert b.dtype == np.float32 and b.tolist() == [22, 1, 5]
+    G[0] = ex["attacked_gradient_client1"]
+    assert O.rar_sum_ring_order(G).tolist() == ex["attacked_aggregate"]
+    assert C.rar_sum_ring_f32(G).tolist() == ex["attacked_aggregate"]
+
+
+def test_fp32_ring_order_is_c_then_c_plus_1():
+    # Three clients holding (2^24, 1, 1) in EVERY coordinate.  In fp32 2^24 + 1 = 2^24 (tie to
+    # even) and 2 + 2^24 = 2^24 + 2, so the order of the additions shows in the result:
+    #   chunk 0: (2^24 + 1) + 1 = 2^24          order 0, 1, 2
+    #   chunk 1: (1 + 1) + 2^24 = 2^24 + 2      order 1, 2, 0
+    #   chunk 2: (1 + 2^24) + 1 = 2^24          order 2, 0, 1
+    # which is the order the ring example of Sec. 2.2 fixes (Client 1 receives the third
+    # sub-vector from Client 3, adds its own, forwards to Client 2).
+    big = float(2 ** 24)
+    G = np.array([[big] * 6, [1.0] * 6, [1.0] * 6], dtype=np.float32)
+    want = [big, big, big + 2, big + 2, big, big]
+    assert O.rar_sum_ring_order(G).tolist() == want
+    assert C.rar_sum_ring_f32(G).tolist() == want
+    res = O.ring_all_reduce(G, mode="sum", dtype=np.float32)
+    for b in res.buffers:
+        assert b.tolist() == want
+    # the exact sum is 2^24 + 2 everywhere; the fp64 route gives it
+    assert O.rar_sum_direct(G).tolist() == [big + 2] * 6
+    # reversed ring direction (c, c-1, ...) or index order 0..n-1 would give other vectors
+    idx_order = G[0] + G[1] + G[2]
+    assert idx_order.tolist() != want
+
+
+@pytest.mark.parametrize("n,d", [(1, 7), (2, 9), (3, 3), (5, 3), (7, 23), (10, 1000), (20, 1003)])
+def test_fp32_ring_order_equals_the_message_by_message_ring(n, d):
+    rng = np.random.default_rng(7 * n + d)
+    G = (rng.standard_normal((n, d)) * 10.0 ** rng.integers(-3, 4, size=(n, 1))).astype(np.float32)
+    want = O.ring_all_reduce(G, mode="sum", dtype=np.float32)
+    got = O.rar_sum_ring_order(G)
+    for b in want.buffers:                                  # every client ends with the same bits
+        assert np.array_equal(b.view(np.uint32), got.view(np.uint32))
+    assert np.array_equal(C.rar_sum_ring_f32(G).view(np.uint32), got.view(np.uint32))
+    padded = np.full((n, d + 5), np.nan, dtype=np.float32)  # the C loop honours the row pitch
+    padded[:, :d] = G
+    assert np.array_equal(C.rar_sum_ring_f32(padded[:, :d]).view(np.uint32), got.view(np.uint32))
+    mean = O.mean_ring_order(G)
+    assert mean.dtype == np.float32
+    assert np.array_equal(C.rar_sum_ring_f32(G, mean=True).view(np.uint32), mean.view(np.uint32))
+    assert np.array_equal(mean, got / np.float32(n))
+    # forward error bound of recursive summation: |err| <= (n - 1) u sum|g_i| (+ higher order)
+    exact = O.rar_sum_direct(G)
+    bound = (n - 1) * 2.0 ** -24 * np.abs(G.astype(np.float64)).sum(axis=0) * 1.01 + 1e-45
+    assert (np.abs(got.astype(np.float64) - exact) <= bound).all()
+
+
+def test_fp32_ring_misses_the_float_bar_under_cancellation_and_fp64_does_not():
+    # Why the library's default sum accumulates in fp64: with Byzantine rows of magnitude 200
+    # next to benign values of 0.1 (workload 1), a ring of fp32 clients lands outside
+    # 1e-6 + 1e-5 |sum| of the exact sum on some coordinates, while on workload 0 (no large
+    # rows) it stays inside.  Both facts are properties of the arithmetic, not of a kernel.
+    from paper_2501_17392_amd import synth
+    for w, some_outside in ((synth.WORKLOADS[0], False), (synth.WORKLOADS[1].with_d(200_003), True)):
+        G = synth.generate(w, "cpu").numpy()
+        exact = O.rar_sum_direct(G)
+        ring = C.rar_sum_ring_f32(G).astype(np.float64)
+        outside = np.abs(ring - exact) > 1e-6 + 1e-5 * np.abs(exact)
+        assert bool(outside.any()) == some_outside
+        once = exact.astype(np.float32).astype(np.float64)       # fp64 sum rounded once
+        assert (np.abs(once - exact) <= 1e-6 + 1e-5 * np.abs(exact)).all()
+
+
+def test_fp32_ring_order_with_more_clients_than_coordinates():
+    # d < n: chunks d .. n-1 are empty, chunk c < d is the single coordinate c.
+    G = np.arange(1, 1 + 5 * 3, dtype=np.float32).reshape(5, 3)
+    assert O.rar_sum_ring_order(G).tolist() == G.sum(axis=0).tolist()
+    assert C.rar_sum_ring_f32(G).tolist() == G.sum(axis=0).tolist()
+
+
 @pytest.mark.parametrize("n,d,m", [(3, 3, 32), (4, 40, 32), (10, 1000, 16), (5, 25, 8)])
 def test_ring_traffic_matches_table_1(n, d, m):
     # n | d: every client sends exactly 2md(n-1)/n bits in RAR and d(n-1)(m+1)/n in BRACE.
