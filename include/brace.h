@@ -17,8 +17,16 @@
  *
  * Conventions
  *   - Pointers named *_dev are DEVICE pointers; the caller owns every buffer.
- *     The library allocates nothing and keeps no state besides the last error
- *     text (thread-local) and the optional launch tuning (process-wide).
+ *     The library allocates nothing and the calls declared here keep no state
+ *     besides the last error text (thread-local).  Launch tuning, the switch of the
+ *     host-side pointer checks and the measurement aids are process-wide and live in
+ *     brace_tuning.h; no caller of the method needs them.
+ *   - Buffers of one call must not overlap each other, with one exception noted at
+ *     brace_aggregate; a call that sees an overlap returns BRACE_EINVAL.
+ *   - Before a call enqueues anything, every buffer is checked on the host: it must be
+ *     device memory known to the HIP runtime and the bytes the call will touch (from the
+ *     sizes given) must lie inside the allocation that holds the pointer; otherwise the
+ *     call returns BRACE_EINVAL and launches nothing.
  *   - Calls validate on the host, enqueue on `hip_stream` (a hipStream_t passed
  *     as void*; NULL is the default stream) and return without synchronising.
  *     BRACE_OK therefore means "validated and enqueued".
@@ -91,7 +99,9 @@ int brace_comm_cost(int32_t scheme, int64_t m, int64_t n, int64_t d, double* bit
  *   f            number of Byzantine clients the caller assumes, 0 <= f <= n.  Validated only:
  *                Eq. (1) does not depend on it.
  *   out_dev      d fp32 values, each exactly +1.0f or -1.0f.  May be NULL when out_bits_dev or
- *                sums_dev is given.  Must not overlap updates_dev.
+ *                sums_dev is given.
+ * updates_dev, out_dev, out_bits_dev and sums_dev must be pairwise disjoint (checked on the
+ * extents the call addresses: (n-1)*ld + d floats, d floats, 4*ceil(d/32) bytes, d int16).
  */
 int brace_aggregate(const float* updates_dev, int64_t n, int64_t d, int64_t f,
                     const brace_params_t* params, float* out_dev, void* hip_stream);
@@ -131,6 +141,15 @@ int brace_chunk_range(int64_t n, int64_t d, int64_t chunk, int64_t* lo, int64_t*
 int brace_chunk_owner(int64_t n, int64_t chunk, int64_t* owner_client);
 
 /*
+ * Eq. (1) on integers.  A sign-sum S over n clients is an integer in [-n, n], so S > lambda
+ * <=> S >= T with T = floor(lambda) + 1, saturated one step outside that range: T = n + 1 when
+ * no sum can exceed lambda (all -1), T = -n when every sum does (all +1).  This is the
+ * threshold every entry point applies; a caller that holds sign-sums can apply it itself.
+ * Host arithmetic only.  EINVAL for n < 1, a non-finite lambda or a NULL result.
+ */
+int brace_threshold(int64_t n, float lambda, int32_t* threshold);
+
+/*
  * Vote fused with its consumer, the model update of Sec. 2.1 / App. A:
  *     w[k] <- w[k] - eta * GAR(g_1..g_n)[k]        i.e. every coordinate moves by exactly eta.
  * w_dev holds d fp32 model parameters, updated in place (one fp32 rounding per coordinate); it
@@ -161,9 +180,13 @@ int brace_apply_bits(const void* bits_dev, int64_t d, float eta, float* w_dev, v
  *
  * Layout: client i's row at signs_dev + i*ld_words (uint32 words); word pair j of a row is
  * (positive bits, negative bits) of coordinates 32j .. 32j+31, bit b <-> coordinate 32j+b.
- * A row has brace_packed_row_words(d) = 2 * roundup(ceil(d/32), 2) words; padding bits are
- * zero.  ld_words = 0 means exactly that; otherwise a multiple of 4 that is at least that
- * (a multiple of 32, i.e. rows that start on 128-byte lines, runs 1-3 % faster).
+ * A row has brace_packed_row_words(d) = 2 * roundup(ceil(d/32), 2) words of data; padding
+ * bits are zero.  ld_words is the row pitch in words: 0 means brace_packed_row_words(d)
+ * (dense rows); otherwise a multiple of 4 that is at least that.  The recommended pitch is
+ * brace_packed_row_pitch(d), the row words rounded up to a multiple of 32: every row then
+ * starts on a 128-byte line and no line is shared by two rows, which removes the lines that
+ * dense rows make the kernels touch twice; words between the row's data and the pitch are
+ * never read or written.
  * signs_dev must be 16-byte aligned and must not overlap updates_dev.  brace_vote_packed honours lambda, zero_sign and
  * out_bits_dev of params (params->ld is ignored, sums_dev must be NULL); out_dev must be
  * 16-byte aligned and may be NULL when out_bits_dev is given.
@@ -175,6 +198,7 @@ int brace_apply_bits(const void* bits_dev, int64_t d, float eta, float* w_dev, v
  * what one device of a sharded run executes on the planes it received for its chunks.
  */
 int64_t brace_packed_row_words(int64_t d);
+int64_t brace_packed_row_pitch(int64_t d);
 int brace_quantize(const float* updates_dev, int64_t n, int64_t d, int64_t ld,
                    uint32_t* signs_dev, int64_t ld_words, void* hip_stream);
 int brace_vote_packed(const uint32_t* signs_dev, int64_t n, int64_t d, int64_t ld_words, int64_t f,
@@ -199,10 +223,13 @@ int brace_vote_packed_chunks(const uint32_t* signs_dev, int64_t n, int64_t d, in
  *
  * Layout: client i's row at votes_dev + i*ld_words (uint32 words), bit b of word j <->
  * coordinate 32j + b, brace_1bit_row_words(d) = roundup(ceil(d/32), 4) words per row, padding
- * bits zero; ld_words = 0 means exactly that, otherwise a multiple of 4 at least that.
+ * bits zero; ld_words = 0 means exactly that, otherwise a multiple of 4 at least that;
+ * recommended: brace_1bit_row_pitch(d), the row words rounded up to a multiple of 32 (rows
+ * start on 128-byte lines).
  * votes_dev and out_dev 16-byte aligned; votes_dev must not overlap updates_dev.
  */
 int64_t brace_1bit_row_words(int64_t d);
+int64_t brace_1bit_row_pitch(int64_t d);
 int brace_quantize_1bit(const float* updates_dev, int64_t n, int64_t d, int64_t ld, int32_t zero_sign,
                         uint32_t* votes_dev, int64_t ld_words, void* hip_stream);
 int brace_vote_1bit(const uint32_t* votes_dev, int64_t n, int64_t d, int64_t ld_words, int64_t f,
@@ -228,15 +255,27 @@ int brace_consensus_sums(const int16_t* parts_dev, int64_t g, int64_t d, int64_t
 /*
  * The operation BRACE replaces: plain ring-all-reduce aggregation (Sec. 2.2), out[k] =
  * sum_i updates[i][k], or the Mean rule of Sec. 2.1 (sum / n) with mean = 1.  Same streaming
- * shape and chunking as brace_aggregate.  Accumulation is in fp64 and the result is rounded
- * to fp32 once, so it matches an fp64 reference within fp32 rounding whatever the
+ * shape and chunking as brace_aggregate.
+ *
+ * order = 0 (default): accumulation in fp64 over the clients in index order, rounded to fp32
+ * once, so the result matches the exact sum within one fp32 rounding whatever the
  * cancellation between rows.
+ * order = 1: what a ring of fp32 clients delivers (Sec. 2.2 Share-Reduce: every receiver adds
+ * its own sub-vector to the one it received): ring chunk c is accumulated in fp32 in the
+ * order c, c+1, ..., n-1, 0, ..., c-1, one rounding per addition, so the bits depend on the
+ * chunk a coordinate falls in (brace_chunk_range); the mean divides by n once, in fp32.
+ * Bit-identical to that ring; NOT within 1e-5 of the exact sum where large rows cancel.
  */
 typedef struct brace_rar_params {
     uint32_t struct_size;  /* sizeof(brace_rar_params_t); checked                              */
     int32_t  mean;         /* 0: sum (Sec. 2.2), 1: mean (Sec. 2.1)                             */
     int64_t  ld;           /* row pitch in elements; 0 means ld = d                              */
+    int32_t  order;        /* 0: fp64, index order; 1: fp32, ring order of the chunk            */
+    int32_t  reserved;     /* must be 0                                                          */
 } brace_rar_params_t;
+
+/* struct_size, sum, dense rows, order 0. */
+void brace_rar_params_init(brace_rar_params_t* params);
 
 int brace_rar_aggregate(const float* updates_dev, int64_t n, int64_t d,
                         const brace_rar_params_t* params, float* out_dev, void* hip_stream);
@@ -244,61 +283,15 @@ int brace_rar_aggregate_chunk(const float* updates_dev, int64_t n, int64_t d, in
                               const brace_rar_params_t* params, float* out_dev, void* hip_stream);
 
 /*
- * Before a call enqueues anything, every buffer is checked on the host: it must be device
- * memory known to the HIP runtime, and the bytes the call will touch (from the sizes given)
- * must lie inside the allocation that holds the pointer; otherwise the call returns
- * BRACE_EINVAL and launches nothing.  On by default (two runtime queries per buffer; measured
- * 0.3 us of a 4.3 us call); process-wide switch for callers that cannot afford them.
- */
-int brace_set_pointer_checks(int32_t enabled);
-
-/*
  * Optional: does, for the current device, the host-side set-up that the first call of some
- * entry points would otherwise do (a device query; opting the burst-writing kernels in to
- * 128 KiB of LDS).  Callers that capture calls into a HIP graph call it once per device
+ * entry points would otherwise do (a device query; loading the kernels; opting the
+ * burst-writing kernels in to 128 KiB of LDS).  Callers that capture calls into a HIP graph call it once per device
  * before the capture, so that the captured calls only launch kernels.  Launches nothing.
  */
 int brace_init_device(void);
 
 /* Text of the last error on the calling thread ("" if none).  Static storage; do not free. */
 const char* brace_last_error(void);
-
-/*
- * Launch tuning for the streaming kernel (process-wide: a call reads the setting in force when
- * it is made; meant for benchmarks and autotuning).  Every combination produces identical
- * results.
- */
-typedef struct brace_tuning {
-    uint32_t struct_size;  /* sizeof(brace_tuning_t)                                             */
-    int32_t  vec;          /* widest load in dwords: 0 = auto (what alignment allows), 1, 2, 4    */
-    int32_t  cols;         /* loads per lane per row: 1, 2, 4 or 8; 0 = from the size of the range */
-    int32_t  unroll;       /* rows per batch of loads: 2, 4 or 8; 0 = from the size of the range  */
-    int32_t  nontemporal;  /* 1: streaming (non-temporal) loads                                   */
-    int32_t  pipeline;     /* 1: request the next batch of rows before consuming the current one  */
-    int32_t  split_writes; /* fp32 output written by a second, write-only kernel from the bits:   */
-                           /* 0 = for large ranges (default), 1 = never, 2 = whenever possible    */
-    int32_t  rowsplit;     /* the 4 waves of a block share their columns and split the client     */
-                           /* rows (partial results meet in LDS): 0 = for short ranges (default), */
-                           /* 1 = never, 2 = always                                               */
-    int32_t  stage_writes; /* results with no compact form (sum / mean, in-place update, the bit   */
-                           /* planes of brace_quantize) are parked in LDS and written as one      */
-                           /* 128 KiB burst per block:                                            */
-                           /* 0 = for large ranges (default), 1 = never, 2 = whenever possible    */
-} brace_tuning_t;
-
-int brace_set_tuning(const brace_tuning_t* tuning);   /* NULL restores the defaults */
-int brace_get_tuning(brace_tuning_t* tuning);
-
-/*
- * Measurement aids (not part of the method): a streaming read and a plain copy of a buffer
- * of known size, used to calibrate the HBM byte counters and to report the bandwidth a
- * trivially linear access pattern reaches on the same device.  Buffers are device memory,
- * 16-byte aligned, nbytes a multiple of 16.  sink_dev is 4 bytes that are (practically)
- * never written.  Enqueued on hip_stream; no synchronisation.
- */
-int brace_probe_read(const void* src_dev, int64_t nbytes, int32_t nontemporal, void* sink_dev,
-                     void* hip_stream);
-int brace_probe_copy(void* dst_dev, const void* src_dev, int64_t nbytes, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -118,26 +118,31 @@ int oracle_rar_sum(const float *updates, int64_t n, int64_t d, int64_t ld,
  * coordinate k of chunk c is ((g_c + g_{c+1}) + ...) + g_{c-1} (indices mod n), each +
  * rounded to float.  Chunks: the first d mod n hold one coordinate more.  With mean != 0
  * the sum is divided by n once, in float (Mean rule of Sec. 2.1).
+ *
+ * `updates` holds the columns [k0, k0 + width) of the n x d_total matrix (row i at
+ * updates + i*ld), so that a large matrix can be checked in column tiles; the chunk of a
+ * column is that of its position k0 + j in the full vector.  out: width floats.
  */
-int oracle_rar_sum_ring_f32(const float *updates, int64_t n, int64_t d, int64_t ld,
-                            int mean, float *out, int threads)
+int oracle_rar_sum_ring_f32(const float *updates, int64_t n, int64_t width, int64_t ld,
+                            int64_t d_total, int64_t k0, int mean, float *out, int threads)
 {
-    if (!updates || !out || n < 1 || d < 0 || ld < d)
+    if (!updates || !out || n < 1 || width < 0 || ld < width || k0 < 0 || d_total < k0 + width)
         return -1;
-    const int64_t q = d / n, r = d % n;
+    const int64_t q = d_total / n, r = d_total % n;
 #ifdef _OPENMP
     int nt = oracle_threads(threads);
 #pragma omp parallel for num_threads(nt) schedule(static)
 #endif
-    for (int64_t k = 0; k < d; ++k) {
+    for (int64_t j = 0; j < width; ++j) {
+        const int64_t k = k0 + j;
         /* chunk of k: the first r chunks have q + 1 coordinates */
         int64_t c = (k < r * (q + 1)) ? k / (q + 1) : r + (k - r * (q + 1)) / q;
-        volatile float acc = updates[c * ld + k];      /* volatile: one rounding per step */
+        volatile float acc = updates[c * ld + j];      /* volatile: one rounding per step */
         for (int64_t s = 1; s < n; ++s)
-            acc = acc + updates[((c + s) % n) * ld + k];
+            acc = acc + updates[((c + s) % n) * ld + j];
         if (mean)
             acc = acc / (float)n;
-        out[k] = acc;
+        out[j] = acc;
     }
     return 0;
 }

@@ -48,7 +48,8 @@ def load():
         ctypes.POINTER(ctypes.c_double), ctypes.c_int]
     lib.oracle_rar_sum.restype = ctypes.c_int
     lib.oracle_rar_sum_ring_f32.argtypes = [
-        f32p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, f32p, ctypes.c_int]
+        f32p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+        ctypes.c_int, f32p, ctypes.c_int]
     lib.oracle_rar_sum_ring_f32.restype = ctypes.c_int
     _lib = lib
     return lib
@@ -106,13 +107,16 @@ def rar_sum(updates: np.ndarray, scale: float = 1.0, nthreads: int = 0) -> np.nd
     return out
 
 
-def rar_sum_ring_f32(updates: np.ndarray, mean: bool = False, nthreads: int = 0) -> np.ndarray:
-    """Ring-order fp32 sum (or mean) of the client rows through the C oracle."""
+def rar_sum_ring_f32(updates: np.ndarray, mean: bool = False, nthreads: int = 0,
+                     d_total: int | None = None, k0: int = 0) -> np.ndarray:
+    """Ring-order fp32 sum (or mean) of the client rows through the C oracle.  `updates` is
+    the whole (n, d) matrix, or its columns [k0, k0 + width) of a vector of d_total."""
     lib = load()
     n, d, ld = _rows(updates)
     out = np.empty(d, dtype=np.float32)
     rc = lib.oracle_rar_sum_ring_f32(
-        updates.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), n, d, ld, 1 if mean else 0,
+        updates.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), n, d, ld,
+        d if d_total is None else int(d_total), int(k0), 1 if mean else 0,
         out.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), int(nthreads))
     if rc != 0:
         raise ValueError("oracle_rar_sum_ring_f32 rejected its arguments")

@@ -49,6 +49,8 @@ class BraceRarParams(ctypes.Structure):
         ("struct_size", ctypes.c_uint32),
         ("mean", ctypes.c_int32),
         ("ld", ctypes.c_int64),
+        ("order", ctypes.c_int32),
+        ("reserved", ctypes.c_int32),
     ]
 
 
@@ -70,6 +72,7 @@ EXPORTS = (
     "brace_vote_packed_chunks", "brace_aggregate_chunks", "brace_consensus_sums",
     "brace_set_pointer_checks", "brace_init_device", "brace_comm_cost",
     "brace_1bit_row_words", "brace_quantize_1bit", "brace_vote_1bit", "brace_vote_1bit_chunks",
+    "brace_packed_row_pitch", "brace_1bit_row_pitch", "brace_rar_params_init", "brace_threshold",
 )
 
 
@@ -147,7 +150,15 @@ def lib():
     L.brace_vote_1bit.restype = ctypes.c_int
     L.brace_vote_1bit_chunks.argtypes = [vp, i64, i64, i64, i64, i64, i64, pp, vp, vp]
     L.brace_vote_1bit_chunks.restype = ctypes.c_int
+    L.brace_packed_row_pitch.argtypes = [i64]
+    L.brace_packed_row_pitch.restype = i64
+    L.brace_1bit_row_pitch.argtypes = [i64]
+    L.brace_1bit_row_pitch.restype = i64
+    L.brace_threshold.argtypes = [i64, ctypes.c_float, ctypes.POINTER(ctypes.c_int32)]
+    L.brace_threshold.restype = ctypes.c_int
     rp = ctypes.POINTER(BraceRarParams)
+    L.brace_rar_params_init.argtypes = [rp]
+    L.brace_rar_params_init.restype = None
     L.brace_rar_aggregate.argtypes = [vp, i64, i64, rp, vp, vp]
     L.brace_rar_aggregate.restype = ctypes.c_int
     L.brace_rar_aggregate_chunk.argtypes = [vp, i64, i64, i64, rp, vp, vp]
@@ -185,6 +196,13 @@ def brace_chunk_range(n: int, d: int, chunk: int) -> tuple[int, int]:
     return lo.value, hi.value
 
 
+def brace_threshold(n: int, lam: float) -> int:
+    """Integer threshold T of Eq. (1): S > lam <=> S >= T for sign-sums over n clients."""
+    t = ctypes.c_int32()
+    _check(lib().brace_threshold(n, float(lam), ctypes.byref(t)))
+    return t.value
+
+
 def brace_chunk_owner(n: int, chunk: int) -> int:
     o = ctypes.c_int64()
     _check(lib().brace_chunk_owner(n, chunk, ctypes.byref(o)))
@@ -204,12 +222,62 @@ def _ptr(t) -> int | None:
     return None if t is None else t.data_ptr()
 
 
+def _dev(t, name: str, dtypes):
+    """Device pointer of an optional flat buffer after checking what the C side cannot see:
+    that it is a CUDA tensor of the element type the ABI reads or writes, and contiguous.
+    (Sizes are checked by the library against the allocation that holds the pointer.)"""
+    if t is None:
+        return None
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise ValueError(f"{name} must be a CUDA tensor")
+    if t.dtype not in dtypes:
+        raise ValueError(f"{name} must have dtype {' or '.join(str(x) for x in dtypes)}, "
+                         f"not {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+def _f32(t, name, d=0):
+    import torch
+    return _dev(t, name, (torch.float32,))
+
+
+def _i16(t, name, d=0):
+    import torch
+    return _dev(t, name, (torch.int16,))
+
+
+def _bitbuf(t, name, d=0):
+    """Packed result: any integer storage of 4*ceil(d/32) bytes."""
+    import torch
+    return _dev(t, name, (torch.int32, torch.uint8, torch.int8, torch.int16, torch.int64))
+
+
+def _rows(t, name: str, dtype):
+    """(rows, cols, pitch) of a row-major 2-D CUDA tensor with unit column stride."""
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != dtype:
+        raise ValueError(f"{name} must be a CUDA tensor of dtype {dtype}")
+    if t.dim() != 2 or (t.stride(1) != 1 and t.shape[1] > 1):
+        raise ValueError(f"{name} must be 2-D with unit column stride")
+    rows, cols = t.shape
+    if rows > 1 and t.stride(0) < cols:
+        raise ValueError(f"{name}: rows overlap (pitch {t.stride(0)} < {cols} columns)")
+    return rows, cols, (t.stride(0) if rows > 1 else max(cols, 1))
+
+
 def _matrix(updates):
-    if updates.dim() != 2 or updates.stride(1) != 1 and updates.shape[1] > 1:
-        raise ValueError("updates must be (n, d) with unit column stride")
-    n, d = updates.shape
-    ld = updates.stride(0) if n > 1 else max(d, 1)
-    return n, d, ld
+    import torch
+    return _rows(updates, "updates", torch.float32)
+
+
+def _planes(t, name: str):
+    """(n, pitch in words) of a packed matrix; a single row is passed as dense."""
+    import torch
+    n, _, pitch = _rows(t, name, torch.int32)
+    return n, (pitch if n > 1 else 0)
 
 
 def brace_aggregate(updates, f: int, lam: float = 5.0, zero_sign: int = 0, out=None,
@@ -220,8 +288,8 @@ def brace_aggregate(updates, f: int, lam: float = 5.0, zero_sign: int = 0, out=N
     out: float32[d], out_bits: int32/uint8 storage of 4*ceil(d/32) bytes, sums: int16[d].
     """
     n, d, ld = _matrix(updates)
-    p = make_params(lam, zero_sign, ld, _ptr(out_bits), _ptr(sums), rule)
-    _check(lib().brace_aggregate(updates.data_ptr(), n, d, f, ctypes.byref(p), _ptr(out),
+    p = make_params(lam, zero_sign, ld, _bitbuf(out_bits, "out_bits", d), _i16(sums, "sums", d), rule)
+    _check(lib().brace_aggregate(updates.data_ptr(), n, d, f, ctypes.byref(p), _f32(out, "out", d),
                                  _stream_handle(stream)))
     return out
 
@@ -230,9 +298,9 @@ def brace_aggregate_chunk(updates, f: int, chunk: int, lam: float = 5.0, zero_si
                           out=None, out_bits=None, sums=None, stream=None, rule: int = 0):
     """brace_aggregate_chunk of the C ABI; `out` etc. are the FULL length-d vectors."""
     n, d, ld = _matrix(updates)
-    p = make_params(lam, zero_sign, ld, _ptr(out_bits), _ptr(sums), rule)
+    p = make_params(lam, zero_sign, ld, _bitbuf(out_bits, "out_bits", d), _i16(sums, "sums", d), rule)
     _check(lib().brace_aggregate_chunk(updates.data_ptr(), n, d, f, chunk, ctypes.byref(p),
-                                       _ptr(out), _stream_handle(stream)))
+                                       _f32(out, "out", d), _stream_handle(stream)))
     return out
 
 
@@ -267,16 +335,20 @@ def brace_probe_copy(dst, src, stream=None):
     _check(lib().brace_probe_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream_handle(stream)))
 
 
-def brace_rar_aggregate(updates, out, mean: bool = False, chunk: int | None = None, stream=None):
-    """Plain ring-all-reduce sum (or mean) of the n client rows; `out` is the full vector."""
+def brace_rar_aggregate(updates, out, mean: bool = False, chunk: int | None = None, stream=None,
+                        order: int = 0):
+    """Plain ring-all-reduce sum (or mean) of the n client rows; `out` is the full vector.
+    order 0: fp64 accumulation in index order; order 1: fp32 in the ring order of each chunk."""
     n, d, ld = _matrix(updates)
-    p = BraceRarParams(ctypes.sizeof(BraceRarParams), 1 if mean else 0, ld)
+    p = BraceRarParams()
+    lib().brace_rar_params_init(ctypes.byref(p))
+    p.mean, p.ld, p.order = (1 if mean else 0), ld, int(order)
     if chunk is None:
-        _check(lib().brace_rar_aggregate(updates.data_ptr(), n, d, ctypes.byref(p), _ptr(out),
-                                         _stream_handle(stream)))
+        _check(lib().brace_rar_aggregate(updates.data_ptr(), n, d, ctypes.byref(p),
+                                         _f32(out, "out", d), _stream_handle(stream)))
     else:
         _check(lib().brace_rar_aggregate_chunk(updates.data_ptr(), n, d, chunk, ctypes.byref(p),
-                                               _ptr(out), _stream_handle(stream)))
+                                               _f32(out, "out", d), _stream_handle(stream)))
     return out
 
 
@@ -285,26 +357,28 @@ def brace_aggregate_update(updates, f: int, w, eta: float, lam: float = 5.0, zer
                            rule: int = 0):
     """Vote fused with the model update w <- w - eta * result (in place); returns w."""
     n, d, ld = _matrix(updates)
-    p = make_params(lam, zero_sign, ld, _ptr(out_bits), _ptr(sums), rule)
+    p = make_params(lam, zero_sign, ld, _bitbuf(out_bits, "out_bits", d), _i16(sums, "sums", d), rule)
     if chunk is None:
         _check(lib().brace_aggregate_update(updates.data_ptr(), n, d, f, ctypes.byref(p),
-                                            float(eta), _ptr(w), _stream_handle(stream)))
+                                            float(eta), _f32(w, "w", d), _stream_handle(stream)))
     else:
         _check(lib().brace_aggregate_update_chunk(updates.data_ptr(), n, d, f, chunk,
-                                                  ctypes.byref(p), float(eta), _ptr(w),
+                                                  ctypes.byref(p), float(eta), _f32(w, "w", d),
                                                   _stream_handle(stream)))
     return w
 
 
 def brace_expand_bits(bits, d: int, out, stream=None):
     """Packed result -> d floats of +-1.0f."""
-    _check(lib().brace_expand_bits(_ptr(bits), d, _ptr(out), _stream_handle(stream)))
+    _check(lib().brace_expand_bits(_bitbuf(bits, "bits", d), d, _f32(out, "out", d),
+                                   _stream_handle(stream)))
     return out
 
 
 def brace_apply_bits(bits, d: int, eta: float, w, stream=None):
     """Packed result applied to a model copy: w <- w - eta * (+-1)."""
-    _check(lib().brace_apply_bits(_ptr(bits), d, float(eta), _ptr(w), _stream_handle(stream)))
+    _check(lib().brace_apply_bits(_bitbuf(bits, "bits", d), d, float(eta), _f32(w, "w", d),
+                                  _stream_handle(stream)))
     return w
 
 
@@ -312,10 +386,17 @@ def brace_packed_row_words(d: int) -> int:
     return int(lib().brace_packed_row_words(d))
 
 
+def brace_packed_row_pitch(d: int) -> int:
+    """Recommended row pitch (words) of the two-plane matrix: rows start on 128-byte lines."""
+    return int(lib().brace_packed_row_pitch(d))
+
+
 def brace_quantize(updates, signs, stream=None):
     """Phase I kept as data: (n, d) floats -> (n, brace_packed_row_words(d)) int32 bit planes."""
     n, d, ld = _matrix(updates)
-    ld_words = signs.stride(0) if n > 1 else 0
+    rows, ld_words = _planes(signs, "signs")
+    if rows != n:
+        raise ValueError("signs must have one row per client")
     _check(lib().brace_quantize(updates.data_ptr(), n, d, ld, signs.data_ptr(), ld_words,
                                 _stream_handle(stream)))
     return signs
@@ -324,22 +405,20 @@ def brace_quantize(updates, signs, stream=None):
 def brace_vote_packed(signs, d: int, f: int, lam: float = 5.0, zero_sign: int = 0, out=None,
                       out_bits=None, stream=None):
     """Phases II-IV on the packed sign planes; same result as brace_aggregate on the floats."""
-    n = signs.shape[0]
-    ld_words = signs.stride(0) if n > 1 else 0
-    p = make_params(lam, zero_sign, 0, _ptr(out_bits), None)
-    _check(lib().brace_vote_packed(signs.data_ptr(), n, d, ld_words, f, ctypes.byref(p), _ptr(out),
-                                   _stream_handle(stream)))
+    n, ld_words = _planes(signs, "signs")
+    p = make_params(lam, zero_sign, 0, _bitbuf(out_bits, "out_bits", d), None)
+    _check(lib().brace_vote_packed(signs.data_ptr(), n, d, ld_words, f, ctypes.byref(p),
+                                   _f32(out, "out", d), _stream_handle(stream)))
     return out
 
 
 def brace_vote_packed_chunk(signs, d: int, f: int, chunk: int, lam: float = 5.0, zero_sign: int = 0,
                             out=None, out_bits=None, stream=None):
     """brace_vote_packed for one ring chunk; `out` / `out_bits` are the FULL vectors."""
-    n = signs.shape[0]
-    ld_words = signs.stride(0) if n > 1 else 0
-    p = make_params(lam, zero_sign, 0, _ptr(out_bits), None)
+    n, ld_words = _planes(signs, "signs")
+    p = make_params(lam, zero_sign, 0, _bitbuf(out_bits, "out_bits", d), None)
     _check(lib().brace_vote_packed_chunk(signs.data_ptr(), n, d, ld_words, f, chunk, ctypes.byref(p),
-                                         _ptr(out), _stream_handle(stream)))
+                                         _f32(out, "out", d), _stream_handle(stream)))
     return out
 
 
@@ -347,11 +426,11 @@ def brace_vote_packed_chunks(signs, d: int, f: int, chunk_begin: int, chunk_end:
                              lam: float = 5.0, zero_sign: int = 0, out=None, out_bits=None,
                              stream=None):
     """brace_vote_packed for a run of consecutive ring chunks in one call."""
-    n = signs.shape[0]
-    ld_words = signs.stride(0) if n > 1 else 0
-    p = make_params(lam, zero_sign, 0, _ptr(out_bits), None)
+    n, ld_words = _planes(signs, "signs")
+    p = make_params(lam, zero_sign, 0, _bitbuf(out_bits, "out_bits", d), None)
     _check(lib().brace_vote_packed_chunks(signs.data_ptr(), n, d, ld_words, f, chunk_begin, chunk_end,
-                                          ctypes.byref(p), _ptr(out), _stream_handle(stream)))
+                                          ctypes.byref(p), _f32(out, "out", d),
+                                          _stream_handle(stream)))
     return out
 
 
@@ -359,45 +438,49 @@ def brace_1bit_row_words(d: int) -> int:
     return int(lib().brace_1bit_row_words(d))
 
 
+def brace_1bit_row_pitch(d: int) -> int:
+    """Recommended row pitch (words) of the one-bit matrix: rows start on 128-byte lines."""
+    return int(lib().brace_1bit_row_pitch(d))
+
+
 def brace_quantize_1bit(updates, zero_sign: int, votes, stream=None):
     """Phase I as one bit per dimension (zero_sign = +1 or -1): bit = 1 where the vote is +1."""
     n, d, ld = _matrix(updates)
-    ld_words = votes.stride(0) if n > 1 else 0
-    _check(lib().brace_quantize_1bit(updates.data_ptr(), n, d, ld, int(zero_sign), _ptr(votes),
+    rows, ld_words = _planes(votes, "votes")
+    if rows != n:
+        raise ValueError("votes must have one row per client")
+    _check(lib().brace_quantize_1bit(updates.data_ptr(), n, d, ld, int(zero_sign), votes.data_ptr(),
                                      ld_words, _stream_handle(stream)))
     return votes
 
 
 def brace_vote_1bit(votes, d: int, f: int, lam: float = 5.0, out=None, out_bits=None, stream=None):
     """Phases II-IV on the one-bit votes; equals brace_aggregate with the zero_sign they were made with."""
-    n = votes.shape[0]
-    ld_words = votes.stride(0) if n > 1 else 0
-    p = make_params(lam, 0, 0, _ptr(out_bits), None)
-    _check(lib().brace_vote_1bit(votes.data_ptr(), n, d, ld_words, f, ctypes.byref(p), _ptr(out),
-                                 _stream_handle(stream)))
+    n, ld_words = _planes(votes, "votes")
+    p = make_params(lam, 0, 0, _bitbuf(out_bits, "out_bits", d), None)
+    _check(lib().brace_vote_1bit(votes.data_ptr(), n, d, ld_words, f, ctypes.byref(p),
+                                 _f32(out, "out", d), _stream_handle(stream)))
     return out
 
 
 def brace_vote_1bit_chunks(votes, d: int, f: int, chunk_begin: int, chunk_end: int, lam: float = 5.0,
                            out=None, out_bits=None, stream=None):
     """brace_vote_1bit for a run of consecutive ring chunks; `out` / `out_bits` are the FULL vectors."""
-    n = votes.shape[0]
-    ld_words = votes.stride(0) if n > 1 else 0
-    p = make_params(lam, 0, 0, _ptr(out_bits), None)
+    n, ld_words = _planes(votes, "votes")
+    p = make_params(lam, 0, 0, _bitbuf(out_bits, "out_bits", d), None)
     _check(lib().brace_vote_1bit_chunks(votes.data_ptr(), n, d, ld_words, f, chunk_begin, chunk_end,
-                                        ctypes.byref(p), _ptr(out), _stream_handle(stream)))
+                                        ctypes.byref(p), _f32(out, "out", d),
+                                        _stream_handle(stream)))
     return out
 
 
 def brace_consensus_sums(parts, lam: float = 5.0, out=None, out_bits=None, stream=None):
     """Phase III on (g, d) int16 partial sign-sums: Eq. (1) applied to their column sums."""
-    if parts.dim() != 2 or parts.stride(1) != 1 and parts.shape[1] > 1:
-        raise ValueError("parts must be (g, d) with unit column stride")
-    g, d = parts.shape
-    ld = parts.stride(0) if g > 1 else 0
-    p = make_params(lam, 0, 0, _ptr(out_bits), None)
-    _check(lib().brace_consensus_sums(_ptr(parts), g, d, ld, ctypes.byref(p), _ptr(out),
-                                      _stream_handle(stream)))
+    import torch
+    g, d, ld = _rows(parts, "parts", torch.int16)
+    p = make_params(lam, 0, 0, _bitbuf(out_bits, "out_bits", d), None)
+    _check(lib().brace_consensus_sums(parts.data_ptr(), g, d, ld if g > 1 else 0, ctypes.byref(p),
+                                      _f32(out, "out", d), _stream_handle(stream)))
     return out
 
 
@@ -405,9 +488,10 @@ def brace_aggregate_chunks(updates, f: int, chunk_begin: int, chunk_end: int, la
                            zero_sign: int = 0, out=None, out_bits=None, sums=None, stream=None):
     """A run of consecutive ring chunks in one launch; `out` etc. are the FULL vectors."""
     n, d, ld = _matrix(updates)
-    p = make_params(lam, zero_sign, ld, _ptr(out_bits), _ptr(sums))
+    p = make_params(lam, zero_sign, ld, _bitbuf(out_bits, "out_bits", d), _i16(sums, "sums", d))
     _check(lib().brace_aggregate_chunks(updates.data_ptr(), n, d, f, chunk_begin, chunk_end,
-                                        ctypes.byref(p), _ptr(out), _stream_handle(stream)))
+                                        ctypes.byref(p), _f32(out, "out", d),
+                                        _stream_handle(stream)))
     return out
 
 

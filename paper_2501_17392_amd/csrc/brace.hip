@@ -14,6 +14,7 @@
 #include <mutex>
 
 #include "brace.h"
+#include "brace_tuning.h"
 #include "ops.hpp"
 #include "packed.hpp"
 
@@ -405,8 +406,50 @@ int check_extent(int64_t rows, int64_t pitch, int64_t elem_bytes)
     return BRACE_OK;
 }
 
-int validate(const float* updates, int64_t n, int64_t d, int64_t f, const brace_params_t* p,
-             const float* out, int64_t* ld_out, int* thresh_out)
+// Eq. (1) on an integer sign-sum S with |S| <= limit:  S > lambda  <=>  S >= floor(lambda) + 1.
+// The threshold saturates one step outside the range S can take: limit + 1 is never reached
+// (all -1), -limit always is (all +1).  Every entry point that applies Eq. (1) takes its
+// threshold from here.
+int threshold_from_lambda(int64_t limit, float lambda)
+{
+    const double t = std::floor((double)lambda) + 1.0;
+    if (t > (double)limit)
+        return (int)limit + 1;
+    if (t < -(double)limit)
+        return -(int)limit;
+    return (int)t;
+}
+
+// The buffers of one call, as byte intervals.  Two of them may not overlap unless both are
+// only read; an overlap is reported with both names.
+struct Span {
+    const void* ptr;
+    int64_t bytes;
+    const char* name;
+    bool written;
+};
+
+int check_disjoint(const Span* spans, int count)
+{
+    for (int i = 0; i < count; ++i) {
+        if (!spans[i].ptr || spans[i].bytes <= 0)
+            continue;
+        const uintptr_t a0 = reinterpret_cast<uintptr_t>(spans[i].ptr);
+        const uintptr_t a1 = a0 + (uintptr_t)spans[i].bytes;
+        for (int j = i + 1; j < count; ++j) {
+            if (!spans[j].ptr || spans[j].bytes <= 0 || !(spans[i].written || spans[j].written))
+                continue;
+            const uintptr_t b0 = reinterpret_cast<uintptr_t>(spans[j].ptr);
+            const uintptr_t b1 = b0 + (uintptr_t)spans[j].bytes;
+            if (a0 < b1 && b0 < a1)
+                return fail(BRACE_EINVAL, "%s overlaps %s", spans[j].name, spans[i].name);
+        }
+    }
+    return BRACE_OK;
+}
+
+// Checks of the consensus parameters shared by every entry point that takes brace_params_t.
+int check_params(const brace_params_t* p, int64_t n, int64_t d, int64_t f)
 {
     if (!p)
         return fail(BRACE_EINVAL, "params is NULL");
@@ -429,12 +472,22 @@ int validate(const float* updates, int64_t n, int64_t d, int64_t f, const brace_
         return fail(BRACE_EINVAL, "rule must be 0 (Eq. (1)) or 1 (majority sign)");
     if (p->rule == 1 && p->out_bits_dev)
         return fail(BRACE_EINVAL, "the majority rule is three-valued and has no 1-bit form");
+    return BRACE_OK;
+}
+
+int validate(const float* updates, int64_t n, int64_t d, int64_t f, const brace_params_t* p,
+             const float* out, int64_t* ld_out, int* thresh_out)
+{
+    const int rc = check_params(p, n, d, f);
+    if (rc != BRACE_OK)
+        return rc;
     if (p->ld != 0 && p->ld < d)
         return fail(BRACE_EINVAL, "ld = %lld is smaller than d = %lld", (long long)p->ld,
                     (long long)d);
-    *ld_out = p->ld ? p->ld : d;
+    const int64_t ld = p->ld ? p->ld : d;
+    *ld_out = ld;
     *thresh_out = 0;
-    if (check_extent(n, *ld_out, 4) != BRACE_OK)
+    if (check_extent(n, ld, 4) != BRACE_OK)
         return BRACE_ERANGE;
     if (d == 0)
         return BRACE_OK;       // nothing is read or written, so empty buffers may be NULL
@@ -448,24 +501,17 @@ int validate(const float* updates, int64_t n, int64_t d, int64_t f, const brace_
         return fail(BRACE_EINVAL, "out_bits_dev must be 4-byte aligned");
     if (p->sums_dev && !aligned_to(p->sums_dev, 2))
         return fail(BRACE_EINVAL, "sums_dev must be 2-byte aligned");
-    const int64_t ld = p->ld ? p->ld : d;
-    if (out && d > 0) {
-        const float* in_end = updates + (n - 1) * ld + d;
-        if (out < in_end && updates < out + d)
-            return fail(BRACE_EINVAL, "out_dev overlaps updates_dev");
-    }
-    *ld_out = ld;
-    const double fl = std::floor((double)p->lambda);
-    int t;
-    if (fl >= (double)n)
-        t = (int)n + 1;            // never reached: all -1
-    else if (fl < -(double)n - 1.0)
-        t = -(int)n;               // always reached: all +1
-    else
-        t = (int)fl + 1;
-    if (p->rule == 1)
-        t = 1;                     // sign(S): +1 iff S >= 1, 0 at S == 0 (set by the kernel)
-    *thresh_out = t;
+    // `out` is the float vector the call writes: out_dev, or w_dev of the fused update.
+    const Span spans[] = {
+        {updates, ((n - 1) * ld + d) * 4, "updates_dev", false},
+        {out, d * 4, "out_dev", true},
+        {p->out_bits_dev, ((d + 31) / 32) * 4, "out_bits_dev", true},
+        {p->sums_dev, d * 2, "sums_dev", true},
+    };
+    if (check_disjoint(spans, 4) != BRACE_OK)
+        return BRACE_EINVAL;
+    // sign(S): +1 iff S >= 1, 0 at S == 0 (set by the kernel)
+    *thresh_out = p->rule == 1 ? 1 : threshold_from_lambda(n, p->lambda);
     return BRACE_OK;
 }
 
@@ -868,6 +914,53 @@ int launch_sum(const float* updates, int64_t n, int64_t d, int64_t ld, double sc
     return check_launch("sum kernel");
 }
 
+// The ring-order fp32 sum over the run of chunks [c_begin, c_end): one grid, the same number
+// of blocks for every chunk (sized for the longest one).
+int launch_ring_sum(const float* updates, int64_t n, int64_t d, int64_t ld, int mean, float* out,
+                    int64_t c_begin, int64_t c_end, hipStream_t stream)
+{
+    if (c_end <= c_begin || d == 0)
+        return BRACE_OK;
+    {
+        // chunks are ascending and contiguous: the run is empty when its first chunk starts at d
+        const int64_t q0 = d / n, r0 = d % n;
+        if (c_begin * q0 + (c_begin < r0 ? c_begin : r0) >= d)
+            return BRACE_OK;
+    }
+    const int rc = check_buffers(updates, n, d, ld, out, nullptr, nullptr, nullptr);
+    if (rc != BRACE_OK)
+        return rc;
+    const brace_tuning_t t = current_tuning();
+    const int v = pick_width(updates, n, ld, out, nullptr, t.vec);
+    RingArgs a;
+    a.ld = ld;
+    a.q = d / n;
+    a.r = d % n;
+    a.n = (int32_t)n;
+    a.mean = mean;
+    a.chunk0 = (int32_t)c_begin;
+    const int64_t slot = 64 * (int64_t)v;
+    const int64_t longest = a.q + (a.r > 0 ? 1 : 0);
+    const int64_t slots = longest / slot;          // upper bound of a chunk's aligned slots
+    const int64_t chunks = c_end - c_begin;
+    const int64_t cus = compute_units() > 0 ? compute_units() : 256;
+    // Long runs per wave pay once the grid still fills the device (about 2 waves per SIMD).
+    const int cols = (t.cols == 0 ? chunks * slots / kRingColsWide >= 8 * cus : t.cols >= kRingColsWide)
+                         ? kRingColsWide : 1;
+    const int64_t per_block = (int64_t)kWaves * cols;
+    // A chunk without an aligned slot is all edge and shorter than two slots.
+    a.edge_blocks = (int32_t)((2 * (slot - 1) + kBlock - 1) / kBlock);
+    const int64_t bpc = a.edge_blocks + (slots + per_block - 1) / per_block;
+    a.blocks_per_chunk = (int32_t)bpc;
+    const int64_t grid = bpc * chunks;
+    if (bpc > 0x7fffffffLL || grid > 0x7fffffffLL)
+        return fail(BRACE_ERANGE, "range needs %lld blocks, more than one launch can hold",
+                    (long long)grid);
+    hipLaunchKernelGGL(brace_ring_pick(v, cols), dim3((unsigned)grid), dim3(kBlock), 0, stream,
+                       updates, a, out);
+    return check_launch("ring-order sum kernel");
+}
+
 int validate_rar(const float* updates, int64_t n, int64_t d, const brace_rar_params_t* p,
                  const float* out, int64_t* ld_out, double* scale_out)
 {
@@ -884,6 +977,9 @@ int validate_rar(const float* updates, int64_t n, int64_t d, const brace_rar_par
         return fail(BRACE_EINVAL, "d must be >= 0 (got %lld)", (long long)d);
     if (p->mean != 0 && p->mean != 1)
         return fail(BRACE_EINVAL, "mean must be 0 (sum) or 1 (mean)");
+    if ((p->order != 0 && p->order != 1) || p->reserved != 0)
+        return fail(BRACE_EINVAL, "order must be 0 (fp64, index order) or 1 (fp32, ring order) "
+                                  "and reserved 0");
     if (p->ld != 0 && p->ld < d)
         return fail(BRACE_EINVAL, "ld = %lld is smaller than d = %lld", (long long)p->ld,
                     (long long)d);
@@ -898,10 +994,9 @@ int validate_rar(const float* updates, int64_t n, int64_t d, const brace_rar_par
         return fail(BRACE_EINVAL, "updates_dev or out_dev is NULL");
     if (!aligned_to(updates, 4) || !aligned_to(out, 4))
         return fail(BRACE_EINVAL, "updates_dev and out_dev must be 4-byte aligned");
-    const float* in_end = updates + (n - 1) * ld + d;
-    if (out < in_end && updates < out + d)
-        return fail(BRACE_EINVAL, "out_dev overlaps updates_dev");
-    return BRACE_OK;
+    const Span spans[] = {{updates, ((n - 1) * ld + d) * 4, "updates_dev", false},
+                          {out, d * 4, "out_dev", true}};
+    return check_disjoint(spans, 2);
 }
 
 }  // namespace
@@ -941,6 +1036,38 @@ int brace_chunk_owner(int64_t n, int64_t chunk, int64_t* owner_client)
     if (chunk < 0 || chunk >= n)
         return fail(BRACE_ERANGE, "chunk %lld outside [0, %lld)", (long long)chunk, (long long)n);
     *owner_client = (chunk + n - 1) % n;
+    return BRACE_OK;
+}
+
+// The run of ring chunks [chunk_begin, chunk_end) as one coordinate range (consecutive chunks
+// are contiguous); an empty run gives lo = hi.
+static int chunk_run_range(int64_t n, int64_t d, int64_t chunk_begin, int64_t chunk_end, int64_t* lo,
+                    int64_t* hi)
+{
+    if (n < 1 || d < 0)
+        return fail(BRACE_EINVAL, "need n >= 1 and d >= 0");
+    if (chunk_begin < 0 || chunk_end > n || chunk_begin > chunk_end)
+        return fail(BRACE_ERANGE, "chunk range [%lld, %lld) outside [0, %lld]",
+                    (long long)chunk_begin, (long long)chunk_end, (long long)n);
+    *lo = *hi = 0;
+    if (chunk_begin == chunk_end)
+        return BRACE_OK;
+    int64_t unused;
+    int rc = brace_chunk_range(n, d, chunk_begin, lo, &unused);
+    if (rc == BRACE_OK)
+        rc = brace_chunk_range(n, d, chunk_end - 1, &unused, hi);
+    return rc;
+}
+
+int brace_threshold(int64_t n, float lambda, int32_t* threshold)
+{
+    if (!threshold)
+        return fail(BRACE_EINVAL, "threshold is NULL");
+    if (n < 1 || !std::isfinite(lambda))
+        return fail(BRACE_EINVAL, "need n >= 1 and a finite lambda");
+    if (n > ((int64_t)1 << 30))
+        return fail(BRACE_ERANGE, "n = %lld is beyond the range of a 32-bit threshold", (long long)n);
+    *threshold = threshold_from_lambda(n, lambda);
     return BRACE_OK;
 }
 
@@ -1000,19 +1127,10 @@ int brace_aggregate_chunks(const float* updates_dev, int64_t n, int64_t d, int64
     int rc = validate(updates_dev, n, d, f, params, out_dev, &ld, &thresh);
     if (rc != BRACE_OK)
         return rc;
-    if (chunk_begin < 0 || chunk_end > n || chunk_begin > chunk_end)
-        return fail(BRACE_ERANGE, "chunk range [%lld, %lld) outside [0, %lld]",
-                    (long long)chunk_begin, (long long)chunk_end, (long long)n);
-    if (chunk_begin == chunk_end)
-        return BRACE_OK;
-    int64_t lo, hi, unused;
-    rc = brace_chunk_range(n, d, chunk_begin, &lo, &unused);
+    int64_t lo, hi;
+    rc = chunk_run_range(n, d, chunk_begin, chunk_end, &lo, &hi);
     if (rc != BRACE_OK)
         return rc;
-    rc = brace_chunk_range(n, d, chunk_end - 1, &unused, &hi);
-    if (rc != BRACE_OK)
-        return rc;
-    // consecutive chunks are contiguous, so a run of chunks is one coordinate range
     return launch_vote(updates_dev, n, d, ld, thresh, params, out_dev, nullptr, 0.0f, lo, hi,
                        static_cast<hipStream_t>(hip_stream));
 }
@@ -1129,17 +1247,49 @@ int brace_apply_bits(const void* bits_dev, int64_t d, float eta, float* w_dev, v
                             static_cast<hipStream_t>(hip_stream));
 }
 
-int64_t brace_packed_row_words(int64_t d)
+// ---------------------------------------------------------------------------------------
+// Quantise-once route.  The two packed forms differ in a few constants only:
+//   two planes (pos, neg): 2 bits per coordinate, a 16-byte lane load covers 64 coordinates;
+//   one bit (vote is +1):  1 bit per coordinate,  a 16-byte lane load covers 128.
+// ---------------------------------------------------------------------------------------
+}  // extern "C"
+
+namespace {
+
+struct PlaneForm {
+    bool two_planes;
+    const char* matrix;         // name of the packed matrix argument in messages
+    int64_t (*row_words)(int64_t);
+    int coords_per_load;        // coordinates in one u32x4 of a row
+};
+
+int64_t roundup_words(int64_t w, int64_t to)
 {
-    if (d < 0)
-        return 0;
-    int64_t w = d / 32 + (d % 32 != 0);        // no overflow for any d
-    w += w & 1;
-    return 2 * w;
+    return w / to * to + (w % to ? to : 0);     // no overflow for any w the callers pass
 }
 
-int brace_quantize(const float* updates_dev, int64_t n, int64_t d, int64_t ld,
-                   uint32_t* signs_dev, int64_t ld_words, void* hip_stream)
+const PlaneForm kTwoPlanes = {true, "signs_dev", brace_packed_row_words, 64};
+const PlaneForm kOneBit = {false, "votes_dev", brace_1bit_row_words, 128};
+
+// Shape checks of a packed matrix of n rows for vectors of d coordinates; resolves ld_words.
+int check_plane_shape(const PlaneForm& form, int64_t n, int64_t d, int64_t* ld_words)
+{
+    if (d > ((int64_t)1 << 45))
+        return fail(BRACE_ERANGE, "d = %lld does not fit the address space", (long long)d);
+    const int64_t row_words = form.row_words(d);
+    if (*ld_words == 0)
+        *ld_words = row_words;
+    if (*ld_words < row_words || (*ld_words & 3))
+        return fail(BRACE_EINVAL, "ld_words must be a multiple of 4 and at least the %lld words "
+                                  "of a row", (long long)row_words);
+    return check_extent(n, *ld_words, 4);
+}
+
+// Phase I as data, both forms: validation, the choice between a store per span and 128 KiB
+// bursts, and the launch.
+int quantize_to_planes(const PlaneForm& form, const float* updates_dev, int64_t n, int64_t d,
+                       int64_t ld, int up_if_not_negative, uint32_t* planes_dev, int64_t ld_words,
+                       hipStream_t stream)
 {
     if (n < 1 || d < 0)
         return fail(BRACE_EINVAL, "need n >= 1 and d >= 0");
@@ -1147,39 +1297,35 @@ int brace_quantize(const float* updates_dev, int64_t n, int64_t d, int64_t ld,
         return fail(BRACE_ERANGE, "n = %lld exceeds BRACE_MAX_CLIENTS", (long long)n);
     if (ld == 0)
         ld = d;
-    if (ld_words == 0)
-        ld_words = brace_packed_row_words(d);
     if (ld < d)
         return fail(BRACE_EINVAL, "ld = %lld is smaller than d = %lld", (long long)ld, (long long)d);
     if (check_extent(n, ld, 4) != BRACE_OK)
         return BRACE_ERANGE;
-    if (ld_words < brace_packed_row_words(d) || (ld_words & 3))
-        return fail(BRACE_EINVAL, "ld_words must be a multiple of 4 and >= brace_packed_row_words(d)");
-    if (check_extent(n, ld_words, 4) != BRACE_OK)
-        return BRACE_ERANGE;
-    if (d == 0)
-        return BRACE_OK;
-    if (!updates_dev || !signs_dev || !aligned_to(updates_dev, 4) || !aligned_to(signs_dev, 16))
-        return fail(BRACE_EINVAL, "updates_dev (4-byte aligned) and signs_dev (16-byte aligned) "
-                                  "must be non-NULL");
-    {
-        const char* in_lo = reinterpret_cast<const char*>(updates_dev);
-        const char* in_hi = in_lo + ((n - 1) * ld + d) * 4;
-        const char* out_lo = reinterpret_cast<const char*>(signs_dev);
-        const char* out_hi = out_lo + ((n - 1) * ld_words + brace_packed_row_words(d)) * 4;
-        if (out_lo < in_hi && in_lo < out_hi)
-            return fail(BRACE_EINVAL, "signs_dev overlaps updates_dev");
-    }
-    int rc = check_device_range(updates_dev, ((n - 1) * ld + d) * 4, "updates_dev");
-    if (rc == BRACE_OK)
-        rc = check_device_range(signs_dev, ((n - 1) * ld_words + brace_packed_row_words(d)) * 4,
-                                "signs_dev");
+    int rc = check_plane_shape(form, n, d, &ld_words);
     if (rc != BRACE_OK)
         return rc;
-    const int64_t spans = (d + kQuantSpan - 1) / kQuantSpan;
-    const int64_t groups = (spans + kQuantGroup - 1) / kQuantGroup;    // per row
+    if (d == 0)
+        return BRACE_OK;
+    if (!updates_dev || !planes_dev || !aligned_to(updates_dev, 4) || !aligned_to(planes_dev, 16))
+        return fail(BRACE_EINVAL, "updates_dev (4-byte aligned) and %s (16-byte aligned) must be "
+                                  "non-NULL", form.matrix);
+    const int64_t row_words = form.row_words(d);
+    const int64_t in_bytes = ((n - 1) * ld + d) * 4;
+    const int64_t out_bytes = ((n - 1) * ld_words + row_words) * 4;
+    const Span spans[] = {{updates_dev, in_bytes, "updates_dev", false},
+                          {planes_dev, out_bytes, form.matrix, true}};
+    if (check_disjoint(spans, 2) != BRACE_OK)
+        return BRACE_EINVAL;
+    rc = check_device_range(updates_dev, in_bytes, "updates_dev");
+    if (rc == BRACE_OK)
+        rc = check_device_range(planes_dev, out_bytes, form.matrix);
+    if (rc != BRACE_OK)
+        return rc;
+
+    const int spans_per_burst = form.two_planes ? kQuantGroup : kVoteGroup;   // 128 KiB either way
+    const int64_t spans_row = (d + kQuantSpan - 1) / kQuantSpan;
+    const int64_t groups = (spans_row + spans_per_burst - 1) / spans_per_burst;    // per row
     const brace_tuning_t t = current_tuning();
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     // The burst kernel runs one block per compute unit at a time (2 MiB of input each), so its
     // blocks come in rounds and a thinly filled last round costs as much as a full one.
     // Measured: ahead by 2-5 % with well filled rounds (n = 64, d = 8 M: 4.0 rounds; n = 8,
@@ -1189,99 +1335,98 @@ int brace_quantize(const float* updates_dev, int64_t n, int64_t d, int64_t ld,
     const int64_t blocks = groups * n;
     const double fill = (double)blocks / (double)((blocks + cus - 1) / cus * cus);
     const bool staged = t.stage_writes == 2 ||
-                        (t.stage_writes == 0 && spans >= kQuantGroup && blocks >= 4 * cus &&
+                        (t.stage_writes == 0 && spans_row >= spans_per_burst && blocks >= 4 * cus &&
                          fill >= 0.9);
     if (staged) {
-        const int64_t grid = groups * n;
-        if (grid > 0x7fffffffLL)
+        if (blocks > 0x7fffffffLL)
             return fail(BRACE_ERANGE, "matrix too large for one launch");
-        constexpr size_t lds = (size_t)kQuantGroup * 64 * sizeof(u32x4);
-        static_assert(lds <= kStageBytes, "quantize stage exceeds the LDS opted in to");
-        rc = allow_stage_lds(reinterpret_cast<const void*>(brace_quantize_staged_kernel));
-        if (rc != BRACE_OK)
-            return rc;
-        hipLaunchKernelGGL(brace_quantize_staged_kernel, dim3((unsigned)grid), dim3(kQuantBlock),
-                           lds, stream, updates_dev, ld, d, signs_dev, ld_words, groups);
+        constexpr size_t lds2 = (size_t)kQuantGroup * 64 * sizeof(u32x4);
+        constexpr size_t lds1 = (size_t)kVoteGroup * 64 * sizeof(u32x2);
+        static_assert(lds2 <= kStageBytes && lds1 <= kStageBytes,
+                      "the staged planes exceed the LDS opted in to");
+        if (form.two_planes) {
+            rc = allow_stage_lds(reinterpret_cast<const void*>(brace_quantize_staged_kernel));
+            if (rc != BRACE_OK)
+                return rc;
+            hipLaunchKernelGGL(brace_quantize_staged_kernel, dim3((unsigned)blocks),
+                               dim3(kQuantBlock), lds2, stream, updates_dev, ld, d, planes_dev,
+                               ld_words, groups);
+        } else {
+            rc = allow_stage_lds(reinterpret_cast<const void*>(brace_quantize_1bit_staged_kernel));
+            if (rc != BRACE_OK)
+                return rc;
+            hipLaunchKernelGGL(brace_quantize_1bit_staged_kernel, dim3((unsigned)blocks),
+                               dim3(kQuantBlock), lds1, stream, updates_dev, ld, d, planes_dev,
+                               ld_words, row_words, groups, up_if_not_negative);
+        }
         return check_launch("staged quantize kernel");
     }
-    const int64_t tasks = spans * n;
+    const int64_t tasks = spans_row * n;
     const int64_t grid = (tasks + kWaves - 1) / kWaves;
     if (grid > 0x7fffffffLL)
         return fail(BRACE_ERANGE, "matrix too large for one launch");
-    hipLaunchKernelGGL(brace_quantize_kernel, dim3((unsigned)grid), dim3(kBlock), 0, stream,
-                       updates_dev, ld, d, signs_dev, ld_words, spans, tasks);
+    if (form.two_planes)
+        hipLaunchKernelGGL(brace_quantize_kernel, dim3((unsigned)grid), dim3(kBlock), 0, stream,
+                           updates_dev, ld, d, planes_dev, ld_words, spans_row, tasks);
+    else
+        hipLaunchKernelGGL(brace_quantize_1bit_kernel, dim3((unsigned)grid), dim3(kBlock), 0,
+                           stream, updates_dev, ld, d, planes_dev, ld_words, row_words, spans_row,
+                           tasks, up_if_not_negative);
     return check_launch("quantize kernel");
 }
 
-// Phases II-IV on the planes over the coordinate range [lo, hi) (the whole vector, one ring
-// chunk, or a run of chunks).
-static int packed_range(const uint32_t* signs_dev, int64_t n, int64_t d, int64_t ld_words, int64_t f,
-                        const brace_params_t* params, float* out_dev, int64_t lo, int64_t hi,
-                        hipStream_t stream)
+// Phases II-IV on packed rows over the coordinate range [lo, hi) (the whole vector, one ring
+// chunk, or a run of chunks), both forms.
+int vote_on_planes(const PlaneForm& form, const uint32_t* planes_dev, int64_t n, int64_t d,
+                   int64_t ld_words, int64_t f, const brace_params_t* params, float* out_dev,
+                   int64_t lo, int64_t hi, hipStream_t stream)
 {
-    // The scalar checks are those of brace_aggregate; the float matrix is replaced by planes.
-    if (!params)
-        return fail(BRACE_EINVAL, "params is NULL");
-    if (params->struct_size != sizeof(brace_params_t))
-        return fail(BRACE_EINVAL, "params->struct_size is %u, expected %zu", params->struct_size,
-                    sizeof(brace_params_t));
-    if (n < 1 || d < 0 || f < 0 || f > n)
-        return fail(BRACE_EINVAL, "need n >= 1, d >= 0 and 0 <= f <= n");
-    if (n > BRACE_MAX_CLIENTS)
-        return fail(BRACE_ERANGE, "n = %lld exceeds BRACE_MAX_CLIENTS", (long long)n);
-    if (!std::isfinite(params->lambda))
-        return fail(BRACE_EINVAL, "lambda must be finite");
-    if (params->zero_sign < -1 || params->zero_sign > 1 || params->rule != 0)
-        return fail(BRACE_EINVAL, "zero_sign must be -1, 0 or +1; the packed vote implements "
-                                  "rule 0 only");
-    if (params->sums_dev)
-        return fail(BRACE_EINVAL, "sign-sums are not produced from packed signs");
-    if (ld_words == 0)
-        ld_words = brace_packed_row_words(d);
-    if (d > ((int64_t)1 << 45))
-        return fail(BRACE_ERANGE, "d = %lld does not fit the address space", (long long)d);
-    if (ld_words < brace_packed_row_words(d) || (ld_words & 3))
-        return fail(BRACE_EINVAL, "ld_words must be a multiple of 4 and >= brace_packed_row_words(d)");
-    if (check_extent(n, ld_words, 4) != BRACE_OK)
-        return BRACE_ERANGE;
+    int rc = check_params(params, n, d, f);
+    if (rc != BRACE_OK)
+        return rc;
+    if (params->rule != 0 || params->sums_dev)
+        return fail(BRACE_EINVAL, "the vote on packed signs implements rule 0 and produces no "
+                                  "sign-sums");
+    rc = check_plane_shape(form, n, d, &ld_words);
+    if (rc != BRACE_OK)
+        return rc;
     if (d == 0 || hi <= lo)
         return BRACE_OK;
     uint32_t* bits = static_cast<uint32_t*>(params->out_bits_dev);
-    if (!signs_dev || !aligned_to(signs_dev, 16))
-        return fail(BRACE_EINVAL, "signs_dev must be non-NULL and 16-byte aligned");
+    if (!planes_dev || !aligned_to(planes_dev, 16))
+        return fail(BRACE_EINVAL, "%s must be non-NULL and 16-byte aligned", form.matrix);
     if (!out_dev && !bits)
         return fail(BRACE_EINVAL, "no output: out_dev and out_bits_dev are both NULL");
     if (out_dev && !aligned_to(out_dev, 16))
-        return fail(BRACE_EINVAL, "out_dev must be 16-byte aligned for the packed vote");
+        return fail(BRACE_EINVAL, "out_dev must be 16-byte aligned for the vote on packed signs");
     if (bits && !aligned_to(bits, 4))
         return fail(BRACE_EINVAL, "out_bits_dev must be 4-byte aligned");
+    const int64_t plane_bytes = ((n - 1) * ld_words + form.row_words(d)) * 4;
+    const Span spans[] = {{planes_dev, plane_bytes, form.matrix, false},
+                          {out_dev, d * 4, "out_dev", true},
+                          {bits, ((d + 31) / 32) * 4, "out_bits_dev", true}};
+    if (check_disjoint(spans, 3) != BRACE_OK)
+        return BRACE_EINVAL;
 
-    const double fl = std::floor((double)params->lambda);
     const int ni = (int)n;
-    int thresh;
-    if (fl >= (double)n)
-        thresh = ni + 1;
-    else if (fl < -(double)n - 1.0)
-        thresh = -ni;
-    else
-        thresh = (int)fl + 1;
+    const int thresh = threshold_from_lambda(n, params->lambda);
     // S >= thresh as X - Y - c >= 0 on the count slices:
-    //   zero_sign  0: S = P - N            X = P, Y = N, c = thresh
-    //   zero_sign +1: S = n - 2N           N <= floor((n - thresh) / 2)   X = 0, Y = N, c = -M
-    //   zero_sign -1: S = 2P - n           P >= ceil((n + thresh) / 2)    X = P, Y = 0, c = Q
+    //   two planes, zero_sign  0: S = P - N    X = P, Y = N, c = thresh
+    //   two planes, zero_sign +1: S = n - 2N   N <= floor((n - thresh) / 2)   X = 0, Y = N, c = -M
+    //   zero_sign -1, or one bit: S = 2P - n   P >= ceil((n + thresh) / 2)    X = P, Y = 0, c = Q
+    // (n + thresh is in [0, 2n + 1]).
     uint32_t mask_p = ~0u, mask_n = ~0u;
     int c = thresh;
-    if (params->zero_sign == 1) {
+    if (form.two_planes && params->zero_sign == 1) {
         mask_p = 0u;
         const int num = ni - thresh;
         c = -(num >= 0 ? num / 2 : -1);
-    } else if (params->zero_sign == -1) {
+    } else if (!form.two_planes || params->zero_sign == -1) {
         mask_n = 0u;
         c = (ni + thresh + 1) / 2;
     }
 
-    int rc = check_device_range(signs_dev, ((n - 1) * ld_words + brace_packed_row_words(d)) * 4,
-                                "signs_dev");
+    rc = check_device_range(planes_dev, plane_bytes, form.matrix);
     if (rc == BRACE_OK)
         rc = check_device_range(out_dev, d * 4, "out_dev");
     if (rc == BRACE_OK)
@@ -1299,22 +1444,31 @@ static int packed_range(const uint32_t* signs_dev, int64_t n, int64_t d, int64_t
         lo_a = hi_a = lo;          // no body: the whole range is edge
     if (hi_a > lo_a) {
         const int64_t d_body = hi_a - lo_a;
-        const int64_t cols4 = whole ? brace_packed_row_words(d) / 4 : d_body / 64;
+        const int64_t cols4 = whole ? form.row_words(d) / 4 : d_body / form.coords_per_load;
         const int64_t grid = (cols4 + kBlock - 1) / kBlock;
         if (grid > 0x7fffffffLL)
             return fail(BRACE_ERANGE, "vector too long for one launch");
         // Bit-words go to the caller's bit array when there is one, else they are parked in out_dev.
         uint32_t* dst = bits ? bits + lo_a / 32 : reinterpret_cast<uint32_t*>(out_dev + lo_a);
-        const int scratch = bits ? 0 : 1;
-        const u32x4* planes = reinterpret_cast<const u32x4*>(signs_dev + lo_a / 16);
-        if (n <= 255)
-            hipLaunchKernelGGL(brace_vote_packed_kernel<8>, dim3((unsigned)grid), dim3(kBlock), 0,
-                               stream, planes, ld_words / 4, ni, cols4, mask_p, mask_n, c, dst,
-                               scratch, d_body);
-        else
-            hipLaunchKernelGGL(brace_vote_packed_kernel<16>, dim3((unsigned)grid), dim3(kBlock), 0,
-                               stream, planes, ld_words / 4, ni, cols4, mask_p, mask_n, c, dst,
-                               scratch, d_body);
+        const int parked = bits ? 0 : 1;
+        const u32x4* rows = reinterpret_cast<const u32x4*>(planes_dev) + lo_a / form.coords_per_load;
+        const int64_t ld4 = ld_words / 4;
+        const bool wide = n > 255;             // 8 counter bits hold up to 255 clients
+        if (form.two_planes) {
+            if (!wide)
+                hipLaunchKernelGGL(brace_vote_packed_kernel<8>, dim3((unsigned)grid), dim3(kBlock), 0,
+                                   stream, rows, ld4, ni, cols4, mask_p, mask_n, c, dst, parked, d_body);
+            else
+                hipLaunchKernelGGL(brace_vote_packed_kernel<16>, dim3((unsigned)grid), dim3(kBlock), 0,
+                                   stream, rows, ld4, ni, cols4, mask_p, mask_n, c, dst, parked, d_body);
+        } else {
+            if (!wide)
+                hipLaunchKernelGGL(brace_vote_1bit_kernel<8>, dim3((unsigned)grid), dim3(kBlock), 0,
+                                   stream, rows, ld4, ni, cols4, c, dst, parked, d_body);
+            else
+                hipLaunchKernelGGL(brace_vote_1bit_kernel<16>, dim3((unsigned)grid), dim3(kBlock), 0,
+                                   stream, rows, ld4, ni, cols4, c, dst, parked, d_body);
+        }
         rc = check_launch("packed vote kernel");
         if (rc != BRACE_OK)
             return rc;
@@ -1336,41 +1490,83 @@ static int packed_range(const uint32_t* signs_dev, int64_t n, int64_t d, int64_t
     const int64_t edge = (lo_a - lo) + (hi_ext - hi_a);
     if (edge > 0) {
         const int64_t tgrid = (edge + kBlock - 1) / kBlock;
-        hipLaunchKernelGGL(brace_packed_edge_kernel, dim3((unsigned)tgrid), dim3(kBlock), 0, stream,
-                           signs_dev, ld_words, ni, thresh, params->zero_sign, out_dev, bits, lo, lo_a,
-                           hi_a, hi, hi_ext);
+        if (form.two_planes)
+            hipLaunchKernelGGL(brace_packed_edge_kernel, dim3((unsigned)tgrid), dim3(kBlock), 0,
+                               stream, planes_dev, ld_words, ni, thresh, params->zero_sign, out_dev,
+                               bits, lo, lo_a, hi_a, hi, hi_ext);
+        else
+            hipLaunchKernelGGL(brace_1bit_edge_kernel, dim3((unsigned)tgrid), dim3(kBlock), 0,
+                               stream, planes_dev, ld_words, ni, thresh, out_dev, bits, lo, lo_a,
+                               hi_a, hi, hi_ext);
         rc = check_launch("packed edge kernel");
     }
     return rc;
 }
 
+}  // namespace
+
+extern "C" {
+
+int64_t brace_packed_row_words(int64_t d)
+{
+    if (d < 0)
+        return 0;
+    int64_t w = d / 32 + (d % 32 != 0);        // no overflow for any d
+    w += w & 1;
+    return 2 * w;
+}
+
+int64_t brace_packed_row_pitch(int64_t d)
+{
+    return roundup_words(brace_packed_row_words(d), 32);
+}
+
+int64_t brace_1bit_row_words(int64_t d)
+{
+    if (d < 0)
+        return 0;
+    return roundup_words(d / 32 + (d % 32 != 0), 4);
+}
+
+int64_t brace_1bit_row_pitch(int64_t d)
+{
+    return roundup_words(brace_1bit_row_words(d), 32);
+}
+
+int brace_quantize(const float* updates_dev, int64_t n, int64_t d, int64_t ld,
+                   uint32_t* signs_dev, int64_t ld_words, void* hip_stream)
+{
+    return quantize_to_planes(kTwoPlanes, updates_dev, n, d, ld, 0, signs_dev, ld_words,
+                              static_cast<hipStream_t>(hip_stream));
+}
+
+int brace_quantize_1bit(const float* updates_dev, int64_t n, int64_t d, int64_t ld, int32_t zero_sign,
+                        uint32_t* votes_dev, int64_t ld_words, void* hip_stream)
+{
+    if (zero_sign != 1 && zero_sign != -1)
+        return fail(BRACE_EINVAL, "the one-bit form needs zero_sign = +1 or -1 (a zero that abstains "
+                                  "needs the two-plane form)");
+    return quantize_to_planes(kOneBit, updates_dev, n, d, ld, zero_sign == 1 ? 1 : 0, votes_dev,
+                              ld_words, static_cast<hipStream_t>(hip_stream));
+}
+
 int brace_vote_packed(const uint32_t* signs_dev, int64_t n, int64_t d, int64_t ld_words, int64_t f,
                       const brace_params_t* params, float* out_dev, void* hip_stream)
 {
-    return packed_range(signs_dev, n, d, ld_words, f, params, out_dev, 0, d < 0 ? 0 : d,
-                        static_cast<hipStream_t>(hip_stream));
+    return vote_on_planes(kTwoPlanes, signs_dev, n, d, ld_words, f, params, out_dev, 0,
+                          d < 0 ? 0 : d, static_cast<hipStream_t>(hip_stream));
 }
 
 int brace_vote_packed_chunks(const uint32_t* signs_dev, int64_t n, int64_t d, int64_t ld_words,
                              int64_t f, int64_t chunk_begin, int64_t chunk_end,
                              const brace_params_t* params, float* out_dev, void* hip_stream)
 {
-    if (n < 1 || d < 0)
-        return fail(BRACE_EINVAL, "need n >= 1 and d >= 0");
-    if (chunk_begin < 0 || chunk_end > n || chunk_begin > chunk_end)
-        return fail(BRACE_ERANGE, "chunk range [%lld, %lld) outside [0, %lld]",
-                    (long long)chunk_begin, (long long)chunk_end, (long long)n);
-    int64_t lo = 0, hi = 0, unused;
-    if (chunk_begin < chunk_end) {
-        int rc = brace_chunk_range(n, d, chunk_begin, &lo, &unused);
-        if (rc == BRACE_OK)
-            rc = brace_chunk_range(n, d, chunk_end - 1, &unused, &hi);
-        if (rc != BRACE_OK)
-            return rc;
-    }
-    // consecutive chunks are contiguous, so a run of chunks is one coordinate range
-    return packed_range(signs_dev, n, d, ld_words, f, params, out_dev, lo, hi,
-                        static_cast<hipStream_t>(hip_stream));
+    int64_t lo, hi;
+    const int rc = chunk_run_range(n, d, chunk_begin, chunk_end, &lo, &hi);
+    if (rc != BRACE_OK)
+        return rc;
+    return vote_on_planes(kTwoPlanes, signs_dev, n, d, ld_words, f, params, out_dev, lo, hi,
+                          static_cast<hipStream_t>(hip_stream));
 }
 
 int brace_vote_packed_chunk(const uint32_t* signs_dev, int64_t n, int64_t d, int64_t ld_words,
@@ -1383,240 +1579,37 @@ int brace_vote_packed_chunk(const uint32_t* signs_dev, int64_t n, int64_t d, int
                                     hip_stream);
 }
 
-int64_t brace_1bit_row_words(int64_t d)
-{
-    if (d < 0)
-        return 0;
-    const int64_t w = d / 32 + (d % 32 != 0);
-    return w / 4 * 4 + (w % 4 ? 4 : 0);
-}
-
-int brace_quantize_1bit(const float* updates_dev, int64_t n, int64_t d, int64_t ld, int32_t zero_sign,
-                        uint32_t* votes_dev, int64_t ld_words, void* hip_stream)
-{
-    if (n < 1 || d < 0)
-        return fail(BRACE_EINVAL, "need n >= 1 and d >= 0");
-    if (n > BRACE_MAX_CLIENTS)
-        return fail(BRACE_ERANGE, "n = %lld exceeds BRACE_MAX_CLIENTS", (long long)n);
-    if (zero_sign != 1 && zero_sign != -1)
-        return fail(BRACE_EINVAL, "the one-bit form needs zero_sign = +1 or -1 (a zero that abstains "
-                                  "needs the two-plane form)");
-    if (ld == 0)
-        ld = d;
-    if (ld < d)
-        return fail(BRACE_EINVAL, "ld = %lld is smaller than d = %lld", (long long)ld, (long long)d);
-    if (check_extent(n, ld, 4) != BRACE_OK)
-        return BRACE_ERANGE;
-    const int64_t row_words = brace_1bit_row_words(d);
-    if (ld_words == 0)
-        ld_words = row_words;
-    if (ld_words < row_words || (ld_words & 3))
-        return fail(BRACE_EINVAL, "ld_words must be a multiple of 4 and >= brace_1bit_row_words(d)");
-    if (check_extent(n, ld_words, 4) != BRACE_OK)
-        return BRACE_ERANGE;
-    if (d == 0)
-        return BRACE_OK;
-    if (!updates_dev || !votes_dev || !aligned_to(updates_dev, 4) || !aligned_to(votes_dev, 16))
-        return fail(BRACE_EINVAL, "updates_dev (4-byte aligned) and votes_dev (16-byte aligned) "
-                                  "must be non-NULL");
-    {
-        const char* in_lo = reinterpret_cast<const char*>(updates_dev);
-        const char* in_hi = in_lo + ((n - 1) * ld + d) * 4;
-        const char* out_lo = reinterpret_cast<const char*>(votes_dev);
-        const char* out_hi = out_lo + ((n - 1) * ld_words + row_words) * 4;
-        if (out_lo < in_hi && in_lo < out_hi)
-            return fail(BRACE_EINVAL, "votes_dev overlaps updates_dev");
-    }
-    int rc = check_device_range(updates_dev, ((n - 1) * ld + d) * 4, "updates_dev");
-    if (rc == BRACE_OK)
-        rc = check_device_range(votes_dev, ((n - 1) * ld_words + row_words) * 4, "votes_dev");
-    if (rc != BRACE_OK)
-        return rc;
-    const int64_t spans = (d + kQuantSpan - 1) / kQuantSpan;
-    const int64_t groups = (spans + kVoteGroup - 1) / kVoteGroup;       // per row
-    const brace_tuning_t t = current_tuning();
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const int up = zero_sign == 1 ? 1 : 0;
-    // Same rule as the two-plane kernel: bursts when the blocks come in well filled rounds.
-    const int64_t cus = compute_units() > 0 ? compute_units() : 256;
-    const int64_t blocks = groups * n;
-    const double fill = (double)blocks / (double)((blocks + cus - 1) / cus * cus);
-    const bool staged = t.stage_writes == 2 ||
-                        (t.stage_writes == 0 && spans >= kVoteGroup && blocks >= 4 * cus &&
-                         fill >= 0.9);
-    if (staged) {
-        if (blocks > 0x7fffffffLL)
-            return fail(BRACE_ERANGE, "matrix too large for one launch");
-        constexpr size_t lds = (size_t)kVoteGroup * 64 * sizeof(u32x2);
-        static_assert(lds <= kStageBytes, "vote stage exceeds the LDS opted in to");
-        rc = allow_stage_lds(reinterpret_cast<const void*>(brace_quantize_1bit_staged_kernel));
-        if (rc != BRACE_OK)
-            return rc;
-        hipLaunchKernelGGL(brace_quantize_1bit_staged_kernel, dim3((unsigned)blocks),
-                           dim3(kQuantBlock), lds, stream, updates_dev, ld, d, votes_dev, ld_words,
-                           row_words, groups, up);
-        return check_launch("staged one-bit quantize kernel");
-    }
-    const int64_t tasks = spans * n;
-    const int64_t grid = (tasks + kWaves - 1) / kWaves;
-    if (grid > 0x7fffffffLL)
-        return fail(BRACE_ERANGE, "matrix too large for one launch");
-    hipLaunchKernelGGL(brace_quantize_1bit_kernel, dim3((unsigned)grid), dim3(kBlock), 0, stream,
-                       updates_dev, ld, d, votes_dev, ld_words, row_words, spans, tasks, up);
-    return check_launch("one-bit quantize kernel");
-}
-
-// Phases II-IV on one-bit votes over the coordinate range [lo, hi).
-static int onebit_range(const uint32_t* votes_dev, int64_t n, int64_t d, int64_t ld_words, int64_t f,
-                        const brace_params_t* params, float* out_dev, int64_t lo, int64_t hi,
-                        hipStream_t stream)
-{
-    if (!params)
-        return fail(BRACE_EINVAL, "params is NULL");
-    if (params->struct_size != sizeof(brace_params_t))
-        return fail(BRACE_EINVAL, "params->struct_size is %u, expected %zu", params->struct_size,
-                    sizeof(brace_params_t));
-    if (n < 1 || d < 0 || f < 0 || f > n)
-        return fail(BRACE_EINVAL, "need n >= 1, d >= 0 and 0 <= f <= n");
-    if (n > BRACE_MAX_CLIENTS)
-        return fail(BRACE_ERANGE, "n = %lld exceeds BRACE_MAX_CLIENTS", (long long)n);
-    if (!std::isfinite(params->lambda))
-        return fail(BRACE_EINVAL, "lambda must be finite");
-    if (params->rule != 0 || params->sums_dev)
-        return fail(BRACE_EINVAL, "the one-bit vote implements rule 0 and produces no sign-sums");
-    if (d > ((int64_t)1 << 45))
-        return fail(BRACE_ERANGE, "d = %lld does not fit the address space", (long long)d);
-    const int64_t row_words = brace_1bit_row_words(d);
-    if (ld_words == 0)
-        ld_words = row_words;
-    if (ld_words < row_words || (ld_words & 3))
-        return fail(BRACE_EINVAL, "ld_words must be a multiple of 4 and >= brace_1bit_row_words(d)");
-    if (check_extent(n, ld_words, 4) != BRACE_OK)
-        return BRACE_ERANGE;
-    if (d == 0 || hi <= lo)
-        return BRACE_OK;
-    uint32_t* bits = static_cast<uint32_t*>(params->out_bits_dev);
-    if (!votes_dev || !aligned_to(votes_dev, 16))
-        return fail(BRACE_EINVAL, "votes_dev must be non-NULL and 16-byte aligned");
-    if (!out_dev && !bits)
-        return fail(BRACE_EINVAL, "no output: out_dev and out_bits_dev are both NULL");
-    if (out_dev && !aligned_to(out_dev, 16))
-        return fail(BRACE_EINVAL, "out_dev must be 16-byte aligned for the one-bit vote");
-    if (bits && !aligned_to(bits, 4))
-        return fail(BRACE_EINVAL, "out_bits_dev must be 4-byte aligned");
-
-    const double fl = std::floor((double)params->lambda);
-    const int ni = (int)n;
-    int thresh;
-    if (fl >= (double)n)
-        thresh = ni + 1;
-    else if (fl < -(double)n - 1.0)
-        thresh = -ni;
-    else
-        thresh = (int)fl + 1;
-    // S = 2P - n >= thresh  <=>  P >= ceil((n + thresh) / 2); n + thresh is in [0, 2n + 1].
-    const int q = (ni + thresh + 1) / 2;
-
-    int rc = check_device_range(votes_dev, ((n - 1) * ld_words + row_words) * 4, "votes_dev");
-    if (rc == BRACE_OK)
-        rc = check_device_range(out_dev, d * 4, "out_dev");
-    if (rc == BRACE_OK)
-        rc = check_device_range(bits, ((d + 31) / 32) * 4, "out_bits_dev");
-    if (rc != BRACE_OK)
-        return rc;
-    // Whole vector: the slice kernel covers everything, ragged end included.  A sub-range is
-    // split like the two-plane vote: whole 1024-coordinate groups through the slice kernel on
-    // offset pointers, the coordinates before and after them one per thread.
-    const bool whole = lo == 0 && hi == d;
-    int64_t lo_a = whole ? 0 : (lo + kGroup - 1) / kGroup * kGroup;
-    int64_t hi_a = whole ? d : hi / kGroup * kGroup;
-    if (lo_a >= hi_a)
-        lo_a = hi_a = lo;          // no body: the whole range is edge
-    if (hi_a > lo_a) {
-        const int64_t d_body = hi_a - lo_a;
-        const int64_t cols4 = whole ? row_words / 4 : d_body / 128;
-        const int64_t grid = (cols4 + kBlock - 1) / kBlock;
-        if (grid > 0x7fffffffLL)
-            return fail(BRACE_ERANGE, "vector too long for one launch");
-        uint32_t* dst = bits ? bits + lo_a / 32 : reinterpret_cast<uint32_t*>(out_dev + lo_a);
-        const int scratch = bits ? 0 : 1;
-        const u32x4* planes = reinterpret_cast<const u32x4*>(votes_dev + lo_a / 32);
-        if (n <= 255)
-            hipLaunchKernelGGL(brace_vote_1bit_kernel<8>, dim3((unsigned)grid), dim3(kBlock), 0,
-                               stream, planes, ld_words / 4, ni, cols4, q, dst, scratch, d_body);
-        else
-            hipLaunchKernelGGL(brace_vote_1bit_kernel<16>, dim3((unsigned)grid), dim3(kBlock), 0,
-                               stream, planes, ld_words / 4, ni, cols4, q, dst, scratch, d_body);
-        rc = check_launch("one-bit vote kernel");
-        if (rc != BRACE_OK)
-            return rc;
-        if (out_dev) {
-            const int64_t groups = (d_body + kGroup - 1) / kGroup;
-            const int64_t egrid = (groups + kWaves - 1) / kWaves;
-            hipLaunchKernelGGL(brace_expand_kernel, dim3((unsigned)egrid), dim3(kBlock), 0, stream,
-                               out_dev, static_cast<const uint32_t*>(bits), lo_a, groups, hi_a);
-            rc = check_launch("expand kernel");
-            if (rc != BRACE_OK)
-                return rc;
-        }
-    }
-    if (whole)
-        return BRACE_OK;
-    int64_t hi_ext = hi;
-    if (bits && hi == d)
-        hi_ext = (d + 31) & ~(int64_t)31;          // the last word's padding bits are zeroed
-    const int64_t edge = (lo_a - lo) + (hi_ext - hi_a);
-    if (edge > 0) {
-        const int64_t tgrid = (edge + kBlock - 1) / kBlock;
-        hipLaunchKernelGGL(brace_1bit_edge_kernel, dim3((unsigned)tgrid), dim3(kBlock), 0, stream,
-                           votes_dev, ld_words, ni, thresh, out_dev, bits, lo, lo_a, hi_a, hi, hi_ext);
-        rc = check_launch("one-bit edge kernel");
-    }
-    return rc;
-}
-
 int brace_vote_1bit(const uint32_t* votes_dev, int64_t n, int64_t d, int64_t ld_words, int64_t f,
                     const brace_params_t* params, float* out_dev, void* hip_stream)
 {
-    return onebit_range(votes_dev, n, d, ld_words, f, params, out_dev, 0, d < 0 ? 0 : d,
-                        static_cast<hipStream_t>(hip_stream));
+    return vote_on_planes(kOneBit, votes_dev, n, d, ld_words, f, params, out_dev, 0, d < 0 ? 0 : d,
+                          static_cast<hipStream_t>(hip_stream));
 }
 
 int brace_vote_1bit_chunks(const uint32_t* votes_dev, int64_t n, int64_t d, int64_t ld_words,
                            int64_t f, int64_t chunk_begin, int64_t chunk_end,
                            const brace_params_t* params, float* out_dev, void* hip_stream)
 {
-    if (n < 1 || d < 0)
-        return fail(BRACE_EINVAL, "need n >= 1 and d >= 0");
-    if (chunk_begin < 0 || chunk_end > n || chunk_begin > chunk_end)
-        return fail(BRACE_ERANGE, "chunk range [%lld, %lld) outside [0, %lld]",
-                    (long long)chunk_begin, (long long)chunk_end, (long long)n);
-    int64_t lo = 0, hi = 0, unused;
-    if (chunk_begin < chunk_end) {
-        int rc = brace_chunk_range(n, d, chunk_begin, &lo, &unused);
-        if (rc == BRACE_OK)
-            rc = brace_chunk_range(n, d, chunk_end - 1, &unused, &hi);
-        if (rc != BRACE_OK)
-            return rc;
-    }
-    return onebit_range(votes_dev, n, d, ld_words, f, params, out_dev, lo, hi,
-                        static_cast<hipStream_t>(hip_stream));
+    int64_t lo, hi;
+    const int rc = chunk_run_range(n, d, chunk_begin, chunk_end, &lo, &hi);
+    if (rc != BRACE_OK)
+        return rc;
+    return vote_on_planes(kOneBit, votes_dev, n, d, ld_words, f, params, out_dev, lo, hi,
+                          static_cast<hipStream_t>(hip_stream));
 }
 
 int brace_consensus_sums(const int16_t* parts_dev, int64_t g, int64_t d, int64_t ld,
                          const brace_params_t* params, float* out_dev, void* hip_stream)
 {
-    if (!params)
-        return fail(BRACE_EINVAL, "params is NULL");
-    if (params->struct_size != sizeof(brace_params_t))
-        return fail(BRACE_EINVAL, "params->struct_size is %u, expected %zu", params->struct_size,
-                    sizeof(brace_params_t));
-    if (g < 1 || d < 0)
+    if (g < 1)
         return fail(BRACE_EINVAL, "need g >= 1 and d >= 0");
     if (g > BRACE_MAX_CLIENTS)
         return fail(BRACE_ERANGE, "g = %lld exceeds BRACE_MAX_CLIENTS", (long long)g);
-    if (!std::isfinite(params->lambda))
-        return fail(BRACE_EINVAL, "lambda must be finite");
+    {
+        const int prc = check_params(params, g, d, 0);      // g stands in for the row count
+        if (prc != BRACE_OK)
+            return prc;
+    }
     if (params->rule != 0 || params->sums_dev)
         return fail(BRACE_EINVAL, "the consensus of partial sums implements rule 0 and produces "
                                   "no sign-sums");
@@ -1636,11 +1629,11 @@ int brace_consensus_sums(const int16_t* parts_dev, int64_t g, int64_t d, int64_t
     if ((out_dev && !aligned_to(out_dev, 4)) || (bits && !aligned_to(bits, 4)))
         return fail(BRACE_EINVAL, "out_dev and out_bits_dev must be 4-byte aligned");
     {
-        const char* in_lo = reinterpret_cast<const char*>(parts_dev);
-        const char* in_hi = in_lo + ((g - 1) * ld + d) * 2;
-        const char* o_lo = reinterpret_cast<const char*>(out_dev);
-        if (out_dev && o_lo < in_hi && in_lo < o_lo + d * 4)
-            return fail(BRACE_EINVAL, "out_dev overlaps parts_dev");
+        const Span spans[] = {{parts_dev, ((g - 1) * ld + d) * 2, "parts_dev", false},
+                              {out_dev, d * 4, "out_dev", true},
+                              {bits, ((d + 31) / 32) * 4, "out_bits_dev", true}};
+        if (check_disjoint(spans, 3) != BRACE_OK)
+            return BRACE_EINVAL;
     }
     int rc = check_device_range(parts_dev, ((g - 1) * ld + d) * 2, "parts_dev");
     if (rc == BRACE_OK)
@@ -1651,9 +1644,7 @@ int brace_consensus_sums(const int16_t* parts_dev, int64_t g, int64_t d, int64_t
         return rc;
 
     // |S| <= g * 32767 < 2^30, so thresholds beyond that range saturate.
-    const double fl = std::floor((double)params->lambda);
-    const double lim = 1073741824.0;
-    const int thresh = fl >= lim ? (int)lim + 1 : fl < -lim - 1.0 ? -(int)lim : (int)fl + 1;
+    const int thresh = threshold_from_lambda((int64_t)1 << 30, params->lambda);
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const bool wide = aligned_to(parts_dev, 16) && (ld % 8 == 0 || g == 1) &&
@@ -1688,6 +1679,14 @@ int brace_consensus_sums(const int16_t* parts_dev, int64_t g, int64_t d, int64_t
     return rc;
 }
 
+void brace_rar_params_init(brace_rar_params_t* params)
+{
+    if (!params)
+        return;
+    std::memset(params, 0, sizeof(*params));
+    params->struct_size = sizeof(brace_rar_params_t);
+}
+
 int brace_rar_aggregate(const float* updates_dev, int64_t n, int64_t d,
                         const brace_rar_params_t* params, float* out_dev, void* hip_stream)
 {
@@ -1696,8 +1695,10 @@ int brace_rar_aggregate(const float* updates_dev, int64_t n, int64_t d,
     const int rc = validate_rar(updates_dev, n, d, params, out_dev, &ld, &scale);
     if (rc != BRACE_OK)
         return rc;
-    return launch_sum(updates_dev, n, d, ld, scale, out_dev, 0, d,
-                      static_cast<hipStream_t>(hip_stream));
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (params->order == 1)
+        return launch_ring_sum(updates_dev, n, d, ld, params->mean, out_dev, 0, n, stream);
+    return launch_sum(updates_dev, n, d, ld, scale, out_dev, 0, d, stream);
 }
 
 int brace_rar_aggregate_chunk(const float* updates_dev, int64_t n, int64_t d, int64_t chunk,
@@ -1712,8 +1713,11 @@ int brace_rar_aggregate_chunk(const float* updates_dev, int64_t n, int64_t d, in
     rc = brace_chunk_range(n, d, chunk, &lo, &hi);
     if (rc != BRACE_OK)
         return rc;
-    return launch_sum(updates_dev, n, d, ld, scale, out_dev, lo, hi,
-                      static_cast<hipStream_t>(hip_stream));
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (params->order == 1)
+        return launch_ring_sum(updates_dev, n, d, ld, params->mean, out_dev, chunk, chunk + 1,
+                               stream);
+    return launch_sum(updates_dev, n, d, ld, scale, out_dev, lo, hi, stream);
 }
 
 const char* brace_last_error(void)

@@ -112,20 +112,14 @@ struct StreamArgs {
     int64_t edge_blocks;    // blocks [0, edge_blocks) run the edges, the rest the body
 };
 
-// One wave folds rows [0, n) starting at `updates` (already offset to its first row) for
-// COLS adjacent slots starting at wave-uniform coordinate k0.
+// One wave folds rows [0, n) starting at `updates` (already offset to its first row) into the
+// states of COLS adjacent slots starting at wave-uniform coordinate k0, in row order.
 template <class Op, int V, int COLS, int RU, bool NT, bool PIPE>
-__device__ __forceinline__ void stream_accumulate(const float* __restrict__ updates, int64_t ld,
-                                                  int n, int64_t k0, int lane,
-                                                  typename Op::State (&st)[COLS][V])
+__device__ __forceinline__ void stream_fold(const float* __restrict__ updates, int64_t ld, int n,
+                                            int64_t k0, int lane,
+                                            typename Op::State (&st)[COLS][V])
 {
     typedef typename Vec<V>::type VT;
-#pragma unroll
-    for (int c = 0; c < COLS; ++c)
-#pragma unroll
-        for (int e = 0; e < V; ++e)
-            Op::init(st[c][e]);
-
     const float* row = updates + k0;            // wave-uniform
     const uint32_t loff = (uint32_t)lane * V;   // per lane, in elements
 
@@ -190,6 +184,20 @@ __device__ __forceinline__ void stream_accumulate(const float* __restrict__ upda
                 Op::add(st[c][e], elem<V>(x[c], e));
         row += ld;
     }
+}
+
+// The same from freshly initialised states.
+template <class Op, int V, int COLS, int RU, bool NT, bool PIPE>
+__device__ __forceinline__ void stream_accumulate(const float* __restrict__ updates, int64_t ld,
+                                                  int n, int64_t k0, int lane,
+                                                  typename Op::State (&st)[COLS][V])
+{
+#pragma unroll
+    for (int c = 0; c < COLS; ++c)
+#pragma unroll
+        for (int e = 0; e < V; ++e)
+            Op::init(st[c][e]);
+    stream_fold<Op, V, COLS, RU, NT, PIPE>(updates, ld, n, k0, lane, st);
 }
 
 // COLS slots from k0: the whole column reduction and its epilogue.  In row-split mode the
@@ -426,6 +434,113 @@ stream_kernel_t<Op> pick_cols(int cols, int ru, int nt, int pipe, int rs)
     case 4: return pick_ru<Op, V, 4>(ru, nt, pipe, rs);
     default: return pick_ru<Op, V, 8>(ru, nt, pipe, rs);
     }
+}
+
+// ---------------------------------------------------------------------------------------
+// Ring-order variant for the plain sum (Sec. 2.2, Share-Reduce).  In the ring, chunk c
+// starts as client c's own sub-vector and every following client adds its own to what it
+// received, so coordinate k of chunk c is ((g_c + g_{c+1}) + ...) + g_{c-1} (indices mod n)
+// in the clients' precision, one fp32 rounding per step.  The start row therefore depends on
+// the chunk, and a grid covers a run of chunks: every chunk gets the same number of blocks,
+// the first `edge_blocks` of them take the chunk's unaligned ends one coordinate per thread,
+// the rest its aligned body; a wave folds rows c .. n-1 and then 0 .. c-1.
+// ---------------------------------------------------------------------------------------
+struct RingArgs {
+    int64_t ld;
+    int64_t q, r;           // chunk c is [c*q + min(c, r), + q + (c < r))
+    int32_t n;
+    int32_t mean;           // 1: divide the sum by n once, in fp32 (Mean rule of Sec. 2.1)
+    int32_t chunk0;         // first chunk of the run
+    int32_t blocks_per_chunk;
+    int32_t edge_blocks;    // per chunk
+};
+
+struct RingSumOp {
+    struct State { float acc; };
+    // -0.0f is the exact identity of fp32 addition (0.0f would turn a sum of -0.0f into +0.0f)
+    __device__ static __forceinline__ void init(State& s) { s.acc = -0.0f; }
+    __device__ static __forceinline__ void add(State& s, float v) { s.acc += v; }
+};
+
+__device__ __forceinline__ float ring_result(float acc, const RingArgs& a)
+{
+    return a.mean ? __fdiv_rn(acc, (float)a.n) : acc;
+}
+
+template <int V, int COLS, int RU>
+__device__ __forceinline__ void ring_slots(const float* __restrict__ updates, const RingArgs& a,
+                                           int c, int64_t k0, int lane, float* __restrict__ out)
+{
+    typedef typename Vec<V>::type VT;
+    RingSumOp::State st[COLS][V];
+#pragma unroll
+    for (int s = 0; s < COLS; ++s)
+#pragma unroll
+        for (int e = 0; e < V; ++e)
+            RingSumOp::init(st[s][e]);
+    stream_fold<RingSumOp, V, COLS, RU, true, true>(updates + (int64_t)c * a.ld, a.ld, a.n - c, k0,
+                                                    lane, st);
+    stream_fold<RingSumOp, V, COLS, RU, true, true>(updates, a.ld, c, k0, lane, st);
+#pragma unroll
+    for (int s = 0; s < COLS; ++s) {
+        VT o;
+#pragma unroll
+        for (int e = 0; e < V; ++e)
+            set_elem<V>(o, e, ring_result(st[s][e].acc, a));
+        store_vec<true>(reinterpret_cast<VT*>(out + k0 + s * (64 * V) + (int64_t)lane * V), o);
+    }
+}
+
+template <int V, int COLS, int RU>
+__global__ void __launch_bounds__(kBlock)
+ring_sum_kernel(const float* __restrict__ updates, const RingArgs a, float* __restrict__ out)
+{
+    const int c = a.chunk0 + (int)(blockIdx.x / (unsigned)a.blocks_per_chunk);   // block-uniform
+    const int t = (int)(blockIdx.x % (unsigned)a.blocks_per_chunk);
+    const int64_t lo = (int64_t)c * a.q + (c < a.r ? c : a.r);
+    const int64_t hi = lo + a.q + (c < a.r ? 1 : 0);
+    constexpr int64_t kSlot = 64 * V;
+    int64_t lo_a = (lo + kSlot - 1) / kSlot * kSlot;
+    int64_t hi_a = hi / kSlot * kSlot;
+    if (lo_a >= hi_a)
+        lo_a = hi_a = lo;                      // no body: the whole chunk is edge
+    if (t < a.edge_blocks) {
+        const int64_t e = (int64_t)t * kBlock + threadIdx.x;
+        const int64_t head = lo_a - lo;
+        const int64_t k = (e < head) ? lo + e : hi_a + (e - head);
+        if (k >= hi)
+            return;
+        float acc = updates[(int64_t)c * a.ld + k];
+        for (int i = c + 1; i < a.n; ++i)
+            acc += updates[(int64_t)i * a.ld + k];
+        for (int i = 0; i < c; ++i)
+            acc += updates[(int64_t)i * a.ld + k];
+        out[k] = ring_result(acc, a);
+        return;
+    }
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int64_t slots = (hi_a - lo_a) / kSlot;
+    const int64_t s0 = ((int64_t)(t - a.edge_blocks) * kWaves + wave) * COLS;
+    if (s0 >= slots)
+        return;
+    if (s0 + COLS <= slots) {
+        ring_slots<V, COLS, RU>(updates, a, c, lo_a + s0 * kSlot, lane, out);
+    } else {
+        for (int64_t s = s0; s < slots; ++s)       // fewer than COLS slots left at the chunk's end
+            ring_slots<V, 1, RU>(updates, a, c, lo_a + s * kSlot, lane, out);
+    }
+}
+
+using ring_sum_kernel_t = void (*)(const float*, const RingArgs, float*);
+
+constexpr int kRingColsWide = 8;
+
+// Long chunks: 8 loads per row, 2 rows per batch; short ones: one load per row, 4 rows.
+template <int V>
+ring_sum_kernel_t pick_ring(int cols)
+{
+    return cols == kRingColsWide ? ring_sum_kernel<V, kRingColsWide, 2> : ring_sum_kernel<V, 1, 4>;
 }
 
 }  // namespace brace_dev

@@ -7,6 +7,7 @@
 #include <stdio.h>
 #include <stdlib.h>
 #include "brace.h"
+#include "brace_tuning.h"
 
 static uint64_t s = 0x9E3779B97F4A7C15ull;
 static uint64_t rnd(void) { s ^= s << 13; s ^= s >> 7; s ^= s << 17; return s; }
@@ -58,11 +59,13 @@ int main(void)
         case 2: rc = brace_aggregate_chunks(in, n, d, f, c, c + (int64_t)(rnd() % 5), &p, out, NULL); break;
         case 3: rc = brace_aggregate_update(in, n, d, f, &p, 0.01f, out, NULL); break;
         case 4: rc = brace_aggregate_update_chunk(in, n, d, f, c, &p, 0.01f, out, NULL); break;
-        case 5: { brace_rar_params_t rp = {sizeof(brace_rar_params_t), (int32_t)(rnd() % 2), p.ld};
+        case 5: { brace_rar_params_t rp = {sizeof(brace_rar_params_t), (int32_t)(rnd() % 2), p.ld,
+                                           (int32_t)(rnd() % 2), 0};
                   rc = (rnd() % 2) ? brace_rar_aggregate(in, n, d, &rp, out, NULL)
                                    : brace_rar_aggregate_chunk(in, n, d, c, &rp, out, NULL); break; }
         case 6: rc = brace_quantize(in, n, d, p.ld, (uint32_t*)(base_aux + 16 * (rnd() % 2)),
-                                    (rnd() % 2) ? 0 : brace_packed_row_words(d) + 4 * (int64_t)(rnd() % 3), NULL); break;
+                                    (rnd() % 3) == 0 ? 0 : (rnd() % 2) ? brace_packed_row_pitch(d)
+                                    : brace_packed_row_words(d) + 4 * (int64_t)(rnd() % 3), NULL); break;
         case 7: p.sums_dev = NULL; p.rule = 0;
                 rc = brace_vote_packed((const uint32_t*)base_in, n, d, 0, f, &p, out ? (float*)base_out : NULL, NULL); break;
         case 8: p.sums_dev = NULL; p.rule = 0;
@@ -72,7 +75,8 @@ int main(void)
                 rc = brace_consensus_sums((const int16_t*)(base_in + 2 * (rnd() % 9)), n, d, p.ld, &p, out, NULL); break;
         case 12: rc = brace_quantize_1bit(in, n, d, p.ld, (int32_t)(rnd() % 4) - 1,
                                           (uint32_t*)(base_aux + 16 * (rnd() % 2)),
-                                          (rnd() % 2) ? 0 : brace_1bit_row_words(d) + 4 * (int64_t)(rnd() % 3), NULL); break;
+                                          (rnd() % 3) == 0 ? 0 : (rnd() % 2) ? brace_1bit_row_pitch(d)
+                                          : brace_1bit_row_words(d) + 4 * (int64_t)(rnd() % 3), NULL); break;
         case 13: p.sums_dev = NULL; p.rule = 0;
                  rc = brace_vote_1bit((const uint32_t*)base_in, n, d, 0, f, &p, out ? (float*)base_out : NULL, NULL); break;
         case 14: p.sums_dev = NULL; p.rule = 0;

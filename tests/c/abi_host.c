@@ -6,6 +6,7 @@
 #include <string.h>
 
 #include "brace.h"
+#include "brace_tuning.h"
 
 #define CHECK(cond)                                                      \
     do {                                                                 \
@@ -38,6 +39,31 @@ int main(void)
     CHECK(brace_chunk_owner(3, 0, &owner) == BRACE_OK && owner == 2);
     CHECK(brace_packed_row_words(25000000) == 2 * 781250);
     CHECK(brace_packed_row_words(33) == 4);
+    /* recommended pitches: whole 128-byte lines per row */
+    CHECK(brace_packed_row_pitch(25000000) == 1562528 && brace_packed_row_pitch(33) == 32);
+    CHECK(brace_packed_row_pitch(0) == 0 && brace_packed_row_pitch(1024) == 64);
+    CHECK(brace_1bit_row_words(25000000) == 781252 && brace_1bit_row_pitch(25000000) == 781280);
+    CHECK(brace_1bit_row_pitch(1) == 32 && brace_1bit_row_pitch(1024) == 32 && brace_1bit_row_pitch(1025) == 64);
+
+    /* Eq. (1) on integers: S > lambda <=> S >= T, saturating one step outside [-n, n] */
+    {
+        int32_t T = 0;
+        CHECK(brace_threshold(100, 5.0f, &T) == BRACE_OK && T == 6);
+        CHECK(brace_threshold(100, 4.999f, &T) == BRACE_OK && T == 5);
+        CHECK(brace_threshold(100, -0.5f, &T) == BRACE_OK && T == 0);
+        CHECK(brace_threshold(100, 99.5f, &T) == BRACE_OK && T == 100);
+        CHECK(brace_threshold(100, 100.0f, &T) == BRACE_OK && T == 101);      /* lambda = n: all -1 */
+        CHECK(brace_threshold(100, 1e30f, &T) == BRACE_OK && T == 101);
+        CHECK(brace_threshold(100, -100.0f, &T) == BRACE_OK && T == -99);
+        CHECK(brace_threshold(100, -100.5f, &T) == BRACE_OK && T == -100);
+        CHECK(brace_threshold(100, -101.0f, &T) == BRACE_OK && T == -100);    /* lambda = -n-1: all +1 */
+        CHECK(brace_threshold(100, -1e30f, &T) == BRACE_OK && T == -100);
+        CHECK(brace_threshold(1, 0.0f, &T) == BRACE_OK && T == 1);
+        CHECK(brace_threshold(BRACE_MAX_CLIENTS, 3e38f, &T) == BRACE_OK && T == BRACE_MAX_CLIENTS + 1);
+        CHECK(brace_threshold(100, NAN, &T) == BRACE_EINVAL);
+        CHECK(brace_threshold(0, 1.0f, &T) == BRACE_EINVAL);
+        CHECK(brace_threshold(100, 1.0f, NULL) == BRACE_EINVAL);
+    }
 
     CHECK(brace_aggregate(fake_in, 4, 100, 1, NULL, fake_out, NULL) == BRACE_EINVAL);
     CHECK(brace_aggregate(NULL, 4, 100, 1, &p, fake_out, NULL) == BRACE_EINVAL);
@@ -51,15 +77,31 @@ int main(void)
     CHECK(brace_aggregate_chunks(fake_in, 4, 100, 1, 2, 2, &p, fake_out, NULL) == BRACE_OK);
     CHECK(brace_aggregate_update(fake_in, 4, 100, 1, &p, INFINITY, fake_out, NULL) == BRACE_EINVAL);
     CHECK(brace_expand_bits(NULL, 0, NULL, NULL) == BRACE_OK);
+    /* buffers of one call must be pairwise disjoint: bits inside out, sums inside the matrix */
+    p.out_bits_dev = (void*)(fake_out + 8);
+    CHECK(brace_aggregate(fake_in, 4, 100, 1, &p, fake_out, NULL) == BRACE_EINVAL);
+    CHECK(strstr(brace_last_error(), "overlaps") != NULL);
+    p.out_bits_dev = NULL;
+    p.sums_dev = (int16_t*)(uintptr_t)(0x7f0000000000ull + 64);
+    CHECK(brace_aggregate(fake_in, 4, 100, 1, &p, fake_out, NULL) == BRACE_EINVAL);
+    p.sums_dev = NULL;
 
     {
         brace_rar_params_t r;
-        r.struct_size = sizeof(r);
+        brace_rar_params_init(&r);
+        CHECK(r.struct_size == sizeof(r) && r.mean == 0 && r.ld == 0 && r.order == 0 && r.reserved == 0);
         r.mean = 2;
-        r.ld = 0;
         CHECK(brace_rar_aggregate(fake_in, 4, 100, &r, fake_out, NULL) == BRACE_EINVAL);
         r.mean = 1;
         CHECK(brace_rar_aggregate(fake_in, 4, 0, &r, fake_out, NULL) == BRACE_OK);
+        r.order = 2;
+        CHECK(brace_rar_aggregate(fake_in, 4, 100, &r, fake_out, NULL) == BRACE_EINVAL);
+        r.order = 1;
+        CHECK(brace_rar_aggregate(fake_in, 4, 0, &r, fake_out, NULL) == BRACE_OK);
+        CHECK(brace_rar_aggregate_chunk(fake_in, 4, 100, 4, &r, fake_out, NULL) == BRACE_ERANGE);
+        /* out inside the matrix: rejected before anything is launched */
+        CHECK(brace_rar_aggregate(fake_in, 4, 100, &r, (float*)(uintptr_t)(0x7f0000000000ull + 40), NULL)
+              == BRACE_EINVAL);
     }
     {
         brace_tuning_t t;

@@ -357,15 +357,24 @@ def test_one_bit_entry_points_validate(L):
 
 
 def test_rar_aggregate_rejects_invalid_arguments(L):
-    def call(inp=FAKE_IN, n=4, d=100, mean=0, ld=0, out=FAKE_OUT, size=None, chunk=None):
-        p = B.BraceRarParams(ctypes.sizeof(B.BraceRarParams) if size is None else size, mean, ld)
+    def call(inp=FAKE_IN, n=4, d=100, mean=0, ld=0, out=FAKE_OUT, size=None, chunk=None, order=0,
+             reserved=0):
+        p = B.BraceRarParams(ctypes.sizeof(B.BraceRarParams) if size is None else size, mean, ld,
+                             order, reserved)
         if chunk is None:
             return L.brace_rar_aggregate(inp, n, d, ctypes.byref(p), out, None)
         return L.brace_rar_aggregate_chunk(inp, n, d, chunk, ctypes.byref(p), out, None)
     E, R = B.BRACE_EINVAL, B.BRACE_ERANGE
-    assert ctypes.sizeof(B.BraceRarParams) == 16
+    assert ctypes.sizeof(B.BraceRarParams) == 24
     assert L.brace_rar_aggregate(FAKE_IN, 4, 100, None, FAKE_OUT, None) == E
     assert call(size=8) == E
+    assert call(size=16) == E                 # the layout before `order` was added
+    assert call(order=2) == E and call(order=-1) == E and call(order=1, reserved=1) == E
+    for order in (0, 1):                      # both orders run the same checks
+        assert call(order=order, d=0) == B.BRACE_OK
+        assert call(order=order, out=FAKE_IN + 40) == E
+        assert call(order=order, chunk=4) == R
+        assert call(order=order, n=7, d=3, chunk=6) == B.BRACE_OK
     assert call(n=0) == E
     assert call(n=B.BRACE_MAX_CLIENTS + 1) == R
     assert call(d=-1) == E

@@ -150,7 +150,10 @@ def test_one_bit_large_workloads_full(idx, col_tile):
     w = synth.WORKLOADS[idx]
     upd = synth.generate(w, DEV)
     zs = 1 if idx != 3 else -1
-    votes = torch.empty(w.n, B.brace_1bit_row_words(w.d), device=DEV, dtype=torch.int32)
+    # rows at the recommended pitch (whole 128-byte lines): the layout bench.py times
+    vw, vp = B.brace_1bit_row_words(w.d), B.brace_1bit_row_pitch(w.d)
+    assert vp % 32 == 0 and 0 <= vp - vw < 32
+    votes = torch.full((w.n, vp), -1, device=DEV, dtype=torch.int32)[:, :vw]
     B.brace_quantize_1bit(upd, zs, votes)
     out = torch.empty(w.d, device=DEV, dtype=torch.float32)
     bits = torch.empty((w.d + 31) // 32, device=DEV, dtype=torch.int32)

@@ -46,9 +46,15 @@ def to_device(g, ld=None, offset=0):
     return view
 
 
-def planes_buffer(n, d, extra_words=0):
+def planes_buffer(n, d, extra_words=0, pitched=False):
+    """n rows of packed planes, filled with -1: dense, with `extra_words` of padding per row,
+    or (pitched) at the recommended pitch, every row on its own 128-byte lines."""
     words = B.brace_packed_row_words(d)
     assert words == O.packed_row_words(d)
+    if pitched:
+        pitch = B.brace_packed_row_pitch(d)
+        assert pitch % 32 == 0 and 0 <= pitch - words < 32
+        extra_words = pitch - words
     store = torch.full((n, words + extra_words), -1, device=DEV, dtype=torch.int32)
     return store[:, :words] if extra_words else store
 
@@ -188,9 +194,10 @@ def test_packed_single_chunk_touches_only_its_range():
 
 @pytest.mark.parametrize("idx,col_tile", [(2, 2_000_000), (3, 2_000_000), (4, 4_000_000)])
 def test_large_workloads_full(idx, col_tile):
+    # rows at the recommended pitch: the layout bench.py times
     w = synth.WORKLOADS[idx]
     upd = synth.generate(w, DEV)
-    signs = planes_buffer(w.n, w.d)
+    signs = planes_buffer(w.n, w.d, pitched=True)
     B.brace_quantize(upd, signs)
     out = torch.empty(w.d, device=DEV, dtype=torch.float32)
     bits = torch.empty((w.d + 31) // 32, device=DEV, dtype=torch.int32)

@@ -521,3 +521,53 @@ def test_calls_from_several_host_threads():
         th.join()
     torch.cuda.synchronize()
     assert not failures, failures
+
+
+def test_binding_refuses_tensors_the_abi_would_misread():
+    # The C side sees only addresses: element type, device and contiguity are the binding's to check.
+    upd = torch.randn(4, 1000, device=DEV)
+    out = torch.empty(1000, device=DEV)
+    with pytest.raises(ValueError):
+        B.brace_aggregate(upd, 0, 0.0, out=torch.empty(1000, device=DEV, dtype=torch.float64))
+    with pytest.raises(ValueError):
+        B.brace_aggregate(upd, 0, 0.0, out=torch.empty(1000))                    # host tensor
+    with pytest.raises(ValueError):
+        B.brace_aggregate(upd, 0, 0.0, out=torch.empty(2000, device=DEV)[::2])  # strided
+    with pytest.raises(ValueError):
+        B.brace_aggregate(upd, 0, 0.0, out=out, sums=torch.empty(1000, device=DEV, dtype=torch.int64))
+    with pytest.raises(ValueError):
+        B.brace_aggregate(upd.double(), 0, 0.0, out=out)
+    with pytest.raises(ValueError):
+        B.brace_aggregate(upd.t(), 0, 0.0, out=out)                              # column-major view
+    with pytest.raises(ValueError):
+        B.brace_vote_packed(torch.zeros(4, 64, device=DEV, dtype=torch.int64), 1000, 0, out=out)
+    with pytest.raises(ValueError):
+        B.brace_consensus_sums(torch.zeros(4, 1000, device=DEV, dtype=torch.int32), out=out)
+    with pytest.raises(ValueError):
+        B.brace_rar_aggregate(upd, torch.empty(1000, device=DEV, dtype=torch.float16))
+    B.brace_aggregate(upd, 0, 0.0, out=out)                                      # a good call still works
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), O.brace_direct(upd.cpu().numpy(), 0.0).out)
+
+
+def test_overlapping_buffers_of_one_call_are_rejected():
+    # Every pair of buffers of a call must be disjoint (the split write path parks bit-words in
+    # `out`, so an overlap would corrupt silently); the call answers EINVAL and launches nothing.
+    n, d = 6, 40_000
+    upd = torch.randn(n, d, device=DEV)
+    out = torch.full((d,), 7.0, device=DEV)
+    as_bits = out[:2048].view(torch.int32)                       # bit array inside out
+    for kw in (dict(out=out, out_bits=as_bits),
+               dict(out=out, sums=out[1000:1000 + d // 2].view(torch.int16)),
+               dict(out=None, out_bits=as_bits, sums=out[:d // 2].view(torch.int16)),
+               dict(out=None, out_bits=upd[2, :2048].view(torch.int32)),
+               dict(out=None, sums=upd[n - 1, d // 2:].view(torch.int16))):
+        with pytest.raises(B.BraceError) as ei:
+            B.brace_aggregate(upd, 0, 0.0, **kw)
+        assert ei.value.code == B.BRACE_EINVAL and "overlaps" in ei.value.text, kw
+    w = torch.zeros(d, device=DEV)
+    with pytest.raises(B.BraceError) as ei:
+        B.brace_aggregate_update(upd, 0, w, 0.1, out_bits=w[:2048].view(torch.int32))
+    assert "overlaps" in ei.value.text
+    torch.cuda.synchronize()
+    assert (out == 7.0).all() and (w == 0.0).all()              # nothing was written

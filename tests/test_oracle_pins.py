@@ -385,6 +385,10 @@ def test_fp32_ring_order_equals_the_message_by_message_ring(n, d):
     padded = np.full((n, d + 5), np.nan, dtype=np.float32)  # the C loop honours the row pitch
     padded[:, :d] = G
     assert np.array_equal(C.rar_sum_ring_f32(padded[:, :d]).view(np.uint32), got.view(np.uint32))
+    for k0, k1 in ((0, d), (0, d // 2), (d // 3, d), (d // 2, d // 2 + 1)):   # column tiles
+        tile = np.ascontiguousarray(G[:, k0:k1])
+        assert np.array_equal(C.rar_sum_ring_f32(tile, d_total=d, k0=k0).view(np.uint32),
+                              got[k0:k1].view(np.uint32))
     mean = O.mean_ring_order(G)
     assert mean.dtype == np.float32
     assert np.array_equal(C.rar_sum_ring_f32(G, mean=True).view(np.uint32), mean.view(np.uint32))
