@@ -165,6 +165,26 @@ int brace_aggregate_update_chunk(const float* updates_dev, int64_t n, int64_t d,
                                  float* w_dev, void* hip_stream);
 
 /*
+ * brace_aggregate_update for callers that can neither allocate device memory nor hand over a
+ * bit array: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * allocation.  Same result as brace_aggregate_update, bit for bit.  The bit-words that pass the
+ * vote from the streaming kernel to the kernel that updates w_dev (what out_bits_dev carries in
+ * brace_aggregate_update) live in a 16 MiB array inside the library's device code, one copy
+ * per device, held until the process ends; the call allocates nothing and frees nothing.
+ *   - d must not exceed BRACE_NOALLOC_MAX_D (BRACE_ERANGE otherwise, nothing launched).
+ *   - params->out_bits_dev must be NULL (BRACE_EINVAL); sums_dev is honoured as usual.
+ *   - Every call on a device uses that device's one array: two calls that overlap in time on
+ *     the same device (different streams or threads) race and give wrong updates.  Calls on
+ *     one stream, or ordered by events, are safe.  Nothing in it needs clearing between calls.
+ *   - The array's address is looked up on the first call on a device (or by
+ *     brace_init_device); do that before a graph capture.
+ */
+#define BRACE_NOALLOC_MAX_D ((int64_t)1 << 27)
+int brace_aggregate_update_noalloc(const float* updates_dev, int64_t n, int64_t d, int64_t f,
+                                   const brace_params_t* params, float eta, float* w_dev,
+                                   void* hip_stream);
+
+/*
  * Receive side of the Share-Only phase (Sec. 3 Phase IV): a client that holds the packed
  * 1-bit result (layout of out_bits_dev, 4*ceil(d/32) bytes) materialises it as d floats of
  * +-1.0f, or applies it to its model copy as w <- w - eta * (+-1).
@@ -285,7 +305,8 @@ int brace_rar_aggregate_chunk(const float* updates_dev, int64_t n, int64_t d, in
 /*
  * Optional: does, for the current device, the host-side set-up that the first call of some
  * entry points would otherwise do (a device query; loading the kernels; opting the
- * burst-writing kernels in to 128 KiB of LDS).  Callers that capture calls into a HIP graph call it once per device
+ * burst-writing kernels in to 128 KiB of LDS; the address of the workspace of
+ * brace_aggregate_update_noalloc).  Callers that capture calls into a HIP graph call it once per device
  * before the capture, so that the captured calls only launch kernels.  Launches nothing.
  */
 int brace_init_device(void);

@@ -73,6 +73,7 @@ EXPORTS = (
     "brace_set_pointer_checks", "brace_init_device", "brace_comm_cost",
     "brace_1bit_row_words", "brace_quantize_1bit", "brace_vote_1bit", "brace_vote_1bit_chunks",
     "brace_packed_row_pitch", "brace_1bit_row_pitch", "brace_rar_params_init", "brace_threshold",
+    "brace_aggregate_update_noalloc",
 )
 
 
@@ -120,6 +121,8 @@ def lib():
     L.brace_aggregate_update.restype = ctypes.c_int
     L.brace_aggregate_update_chunk.argtypes = [vp, i64, i64, i64, i64, pp, ctypes.c_float, vp, vp]
     L.brace_aggregate_update_chunk.restype = ctypes.c_int
+    L.brace_aggregate_update_noalloc.argtypes = [vp, i64, i64, i64, pp, ctypes.c_float, vp, vp]
+    L.brace_aggregate_update_noalloc.restype = ctypes.c_int
     L.brace_expand_bits.argtypes = [vp, i64, vp, vp]
     L.brace_expand_bits.restype = ctypes.c_int
     L.brace_apply_bits.argtypes = [vp, i64, ctypes.c_float, vp, vp]
@@ -365,6 +368,20 @@ def brace_aggregate_update(updates, f: int, w, eta: float, lam: float = 5.0, zer
         _check(lib().brace_aggregate_update_chunk(updates.data_ptr(), n, d, f, chunk,
                                                   ctypes.byref(p), float(eta), _f32(w, "w", d),
                                                   _stream_handle(stream)))
+    return w
+
+
+BRACE_NOALLOC_MAX_D = 1 << 27
+
+
+def brace_aggregate_update_noalloc(updates, f: int, w, eta: float, lam: float = 5.0,
+                                   zero_sign: int = 0, sums=None, stream=None, rule: int = 0):
+    """brace_aggregate_update without a bit array: the bit-words live in the library's own
+    per-device workspace (d <= BRACE_NOALLOC_MAX_D; calls on one device must not overlap)."""
+    n, d, ld = _matrix(updates)
+    p = make_params(lam, zero_sign, ld, None, _i16(sums, "sums", d), rule)
+    _check(lib().brace_aggregate_update_noalloc(updates.data_ptr(), n, d, f, ctypes.byref(p),
+                                                float(eta), _f32(w, "w", d), _stream_handle(stream)))
     return w
 
 

@@ -745,9 +745,48 @@ int check_launch(const char* what)
     return BRACE_OK;
 }
 
+// Library-owned workspace of brace_aggregate_update_noalloc: the bit-words that pass the vote
+// from the streaming kernel to the kernel that updates the model, for callers that cannot
+// hand over a bit array.  One copy per device, held until the process ends.  In host code the
+// array's name is only a handle: the device address is looked up once per device and every
+// launch takes that address as an argument.
+constexpr int64_t kScratchWords = BRACE_NOALLOC_MAX_D / 32;             // 16 MiB
+static __device__ __align__(256) uint32_t scratch[kScratchWords];
+
+std::atomic<uint32_t*> g_scratch_addr[kMaxDevices];                     // null = not looked up yet
+
+int scratch_of_current_device(uint32_t** addr)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(BRACE_EHIP, "no current device");
+    }
+    if (dev < 0 || dev >= kMaxDevices)
+        return fail(BRACE_ERANGE, "device %d is beyond the %d devices the library keeps a "
+                                  "workspace address for", dev, kMaxDevices);
+    uint32_t* known = g_scratch_addr[dev].load(std::memory_order_acquire);
+    if (!known) {
+        void* found = nullptr;
+        const hipError_t err = hipGetSymbolAddress(&found, HIP_SYMBOL(scratch));
+        if (err != hipSuccess || !found) {
+            (void)hipGetLastError();
+            return fail(BRACE_EHIP, "cannot find the workspace on device %d: %s", dev,
+                        hipGetErrorString(err));
+        }
+        known = static_cast<uint32_t*>(found);
+        g_scratch_addr[dev].store(known, std::memory_order_release);   // same value from any thread
+    }
+    *addr = known;
+    return BRACE_OK;
+}
+
+// `ws_bits` (optional) is a workspace of at least ceil(d/32) words that may carry the vote of
+// the fused update from the streaming kernel to the kernel that applies it when the caller
+// gave no bit array; its contents after the call are unspecified.
 int launch_vote(const float* updates, int64_t n, int64_t d, int64_t ld, int thresh,
                 const brace_params_t* p, float* out, float* w, float eta, int64_t lo, int64_t hi,
-                hipStream_t stream)
+                hipStream_t stream, uint32_t* ws_bits = nullptr)
 {
     if (hi <= lo)
         return BRACE_OK;
@@ -767,14 +806,14 @@ int launch_vote(const float* updates, int64_t n, int64_t d, int64_t ld, int thre
     const int64_t groups = hi_s > lo_s ? (hi_s - lo_s) / kGroup : 0;
     // The fused model update can only be split off when the caller gave a bit array: the
     // model itself holds live data and cannot park the bit-words.
-    bool split = (out || w) && (!out || aligned_to(out, 16)) && (!w || (bits && aligned_to(w, 16))) &&
-                 groups > 0 && t.split_writes != 1;
+    bool split = (out || w) && (!out || aligned_to(out, 16)) &&
+                 (!w || ((bits || ws_bits) && aligned_to(w, 16))) && groups > 0 && t.split_writes != 1;
     if (split && t.split_writes != 2)
         split = 4 * n * (hi - lo) >= kSplitMinBytes;
     if (p->rule == 1)
         split = false;             // three values do not fit the bit-words
     if (split && t.split_writes == 0 && t.stage_writes == 0 && n < kStageBelowClients && !bits &&
-        !p->sums_dev) {
+        !ws_bits && !p->sums_dev) {
         // Few clients: prefer bursts from this kernel if the range qualifies for them.
         StreamArgs a0;
         Shape sh0;
@@ -784,9 +823,12 @@ int launch_vote(const float* updates, int64_t n, int64_t d, int64_t ld, int thre
             split = false;
     }
 
+    // Where the body's bit-words go: the caller's array (also the packed output), the
+    // workspace of a split update without one, else (float output) they are parked in `out`.
+    uint32_t* const body_bits = (split && w && !bits) ? ws_bits : bits;
     VoteOp op;
     op.out = out;
-    op.bits = bits;
+    op.bits = body_bits;
     op.sums = p->sums_dev;
     op.w = w;
     op.eta = eta;
@@ -810,7 +852,7 @@ int launch_vote(const float* updates, int64_t n, int64_t d, int64_t ld, int thre
                     (long long)grid);
 
     const int64_t slots = (a.hi_a - a.lo_a) / (64 * (int64_t)v);
-    const bool plain_floats = !split && !bits && !p->sums_dev && (out || w);
+    const bool plain_floats = !split && !body_bits && !p->sums_dev && (out || w);
     const bool stage_ok = plain_floats;
     // Sign-sums alone (the partial sums a device contributes to Share-Reduce) are staged the
     // same way (n = 12, d = 100 M: 852 us with stores per wave, 727 us for the reads alone).
@@ -858,7 +900,7 @@ int launch_vote(const float* updates, int64_t n, int64_t d, int64_t ld, int thre
         }
         if (w) {
             hipLaunchKernelGGL(brace_apply_kernel, dim3((unsigned)egrid), dim3(kBlock), 0, stream,
-                               w, static_cast<const uint32_t*>(bits), eta, a.lo_a, groups);
+                               w, static_cast<const uint32_t*>(body_bits), eta, a.lo_a, groups);
             rc = check_launch("apply kernel");
         }
     }
@@ -1178,6 +1220,34 @@ int brace_aggregate_update_chunk(const float* updates_dev, int64_t n, int64_t d,
         return rc;
     return launch_vote(updates_dev, n, d, ld, thresh, params, nullptr, w_dev, eta, lo, hi,
                        static_cast<hipStream_t>(hip_stream));
+}
+
+int brace_aggregate_update_noalloc(const float* updates_dev, int64_t n, int64_t d, int64_t f,
+                                   const brace_params_t* params, float eta, float* w_dev,
+                                   void* hip_stream)
+{
+    // The size limit first: it does not depend on any other argument.
+    if (d > BRACE_NOALLOC_MAX_D)
+        return fail(BRACE_ERANGE, "d = %lld exceeds BRACE_NOALLOC_MAX_D = %lld, the size of the "
+                                  "library's workspace", (long long)d, (long long)BRACE_NOALLOC_MAX_D);
+    int64_t ld;
+    int thresh;
+    int rc = validate_update(updates_dev, n, d, f, params, eta, w_dev, &ld, &thresh);
+    if (rc != BRACE_OK)
+        return rc;
+    if (params->out_bits_dev)
+        return fail(BRACE_EINVAL, "this entry point takes no bit array (its bit-words live in the "
+                                  "library's own workspace); use brace_aggregate_update");
+    if (d == 0)
+        return BRACE_OK;
+    uint32_t* ws = nullptr;
+    rc = scratch_of_current_device(&ws);
+    if (rc != BRACE_OK)
+        return rc;
+    // Nothing in the workspace has to start at zero: the streaming kernel writes every word
+    // that the applying kernel reads, earlier on the same stream.
+    return launch_vote(updates_dev, n, d, ld, thresh, params, nullptr, w_dev, eta, 0, d,
+                       static_cast<hipStream_t>(hip_stream), ws);
 }
 
 // Receive side of Share-Only: a client holding the packed result materialises it.
@@ -1787,10 +1857,13 @@ int brace_init_device(void)
                 if (rc != BRACE_OK)
                     return rc;
             }
-    const int rc = allow_stage_lds(reinterpret_cast<const void*>(brace_quantize_staged_kernel));
+    int rc = allow_stage_lds(reinterpret_cast<const void*>(brace_quantize_staged_kernel));
+    if (rc == BRACE_OK)
+        rc = allow_stage_lds(reinterpret_cast<const void*>(brace_quantize_1bit_staged_kernel));
     if (rc != BRACE_OK)
         return rc;
-    return allow_stage_lds(reinterpret_cast<const void*>(brace_quantize_1bit_staged_kernel));
+    uint32_t* ws = nullptr;
+    return scratch_of_current_device(&ws);
 }
 
 int brace_set_pointer_checks(int32_t enabled)
