@@ -1515,7 +1515,13 @@ int vote_on_planes(const PlaneForm& form, const uint32_t* planes_dev, int64_t n,
     if (hi_a > lo_a) {
         const int64_t d_body = hi_a - lo_a;
         const int64_t cols4 = whole ? form.row_words(d) / 4 : d_body / form.coords_per_load;
-        const int64_t grid = (cols4 + kBlock - 1) / kBlock;
+        // A wave walks `seq` neighbouring 64-column groups one after the other: up to 3 while
+        // that still leaves about 6 waves for every compute unit.
+        const int64_t groups64 = (cols4 + 63) / 64;
+        const int64_t cus = compute_units() > 0 ? compute_units() : 256;
+        const int64_t fit = groups64 / (6 * cus);
+        const int seq = fit >= 3 ? 3 : fit >= 1 ? (int)fit : 1;
+        const int64_t grid = (groups64 + (int64_t)kWaves * seq - 1) / ((int64_t)kWaves * seq);
         if (grid > 0x7fffffffLL)
             return fail(BRACE_ERANGE, "vector too long for one launch");
         // Bit-words go to the caller's bit array when there is one, else they are parked in out_dev.
@@ -1527,17 +1533,19 @@ int vote_on_planes(const PlaneForm& form, const uint32_t* planes_dev, int64_t n,
         if (form.two_planes) {
             if (!wide)
                 hipLaunchKernelGGL(brace_vote_packed_kernel<8>, dim3((unsigned)grid), dim3(kBlock), 0,
-                                   stream, rows, ld4, ni, cols4, mask_p, mask_n, c, dst, parked, d_body);
+                                   stream, rows, ld4, ni, cols4, seq, mask_p, mask_n, c, dst, parked,
+                                   d_body);
             else
                 hipLaunchKernelGGL(brace_vote_packed_kernel<16>, dim3((unsigned)grid), dim3(kBlock), 0,
-                                   stream, rows, ld4, ni, cols4, mask_p, mask_n, c, dst, parked, d_body);
+                                   stream, rows, ld4, ni, cols4, seq, mask_p, mask_n, c, dst, parked,
+                                   d_body);
         } else {
             if (!wide)
                 hipLaunchKernelGGL(brace_vote_1bit_kernel<8>, dim3((unsigned)grid), dim3(kBlock), 0,
-                                   stream, rows, ld4, ni, cols4, c, dst, parked, d_body);
+                                   stream, rows, ld4, ni, cols4, seq, c, dst, parked, d_body);
             else
                 hipLaunchKernelGGL(brace_vote_1bit_kernel<16>, dim3((unsigned)grid), dim3(kBlock), 0,
-                                   stream, rows, ld4, ni, cols4, c, dst, parked, d_body);
+                                   stream, rows, ld4, ni, cols4, seq, c, dst, parked, d_body);
         }
         rc = check_launch("packed vote kernel");
         if (rc != BRACE_OK)
