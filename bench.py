@@ -134,8 +134,10 @@ def bench_large(B, synth, w, lam, steps, stream, dev, check_cols):
     gen_s = time.perf_counter() - t0
     out = torch.empty(w.d, device=dev, dtype=torch.float32)
     bits = torch.empty((w.d + 31) // 32, device=dev, dtype=torch.int32)
+    # ten untimed calls first: right after the generator's many small kernels the first launches
+    # of a 0.3 ms kernel run several per cent slow
     step_ms, each = time_on_stream(
-        lambda: B.brace_aggregate(upd, w.f, lam, out=out, stream=stream), steps, stream)
+        lambda: B.brace_aggregate(upd, w.f, lam, out=out, stream=stream), steps, stream, warm=10)
     match = oracle_matches(upd, lam, out, sample_windows(w.d, check_cols))
     vote_ms, _ = time_on_stream(
         lambda: B.brace_aggregate(upd, w.f, lam, out=None, out_bits=bits, stream=stream),
@@ -468,7 +470,7 @@ def main():
                 row = bench_small(B, synth, other_w, args.lam, stream, dev)
                 ok = ok and row["gpu_matches_oracle"]
             else:
-                row = bench_large(B, synth, other_w, args.lam, max(5, K // 2), stream, dev, 1 << 20)
+                row = bench_large(B, synth, other_w, args.lam, K, stream, dev, 1 << 20)
                 ok = ok and row["gpu_matches_oracle_on_sample"]
             per.append(row)
         result["per_config"] = per

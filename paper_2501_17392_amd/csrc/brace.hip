@@ -956,50 +956,52 @@ int launch_sum(const float* updates, int64_t n, int64_t d, int64_t ld, double sc
     return check_launch("sum kernel");
 }
 
-// The ring-order fp32 sum over the run of chunks [c_begin, c_end): one grid, the same number
-// of blocks for every chunk (sized for the longest one).
+// The ring-order fp32 sum over the coordinate range [lo, hi): same launch planning as the
+// fp64 sum (tile shape from the size of the range, bursts for large ranges); the kernel finds
+// the chunk, hence the start row, of every run of slots by itself.
 int launch_ring_sum(const float* updates, int64_t n, int64_t d, int64_t ld, int mean, float* out,
-                    int64_t c_begin, int64_t c_end, hipStream_t stream)
+                    int64_t lo, int64_t hi, hipStream_t stream)
 {
-    if (c_end <= c_begin || d == 0)
+    if (hi <= lo)
         return BRACE_OK;
-    {
-        // chunks are ascending and contiguous: the run is empty when its first chunk starts at d
-        const int64_t q0 = d / n, r0 = d % n;
-        if (c_begin * q0 + (c_begin < r0 ? c_begin : r0) >= d)
-            return BRACE_OK;
-    }
     const int rc = check_buffers(updates, n, d, ld, out, nullptr, nullptr, nullptr);
     if (rc != BRACE_OK)
         return rc;
     const brace_tuning_t t = current_tuning();
     const int v = pick_width(updates, n, ld, out, nullptr, t.vec);
-    RingArgs a;
-    a.ld = ld;
-    a.q = d / n;
-    a.r = d % n;
-    a.n = (int32_t)n;
-    a.mean = mean;
-    a.chunk0 = (int32_t)c_begin;
-    const int64_t slot = 64 * (int64_t)v;
-    const int64_t longest = a.q + (a.r > 0 ? 1 : 0);
-    const int64_t slots = longest / slot;          // upper bound of a chunk's aligned slots
-    const int64_t chunks = c_end - c_begin;
-    const int64_t cus = compute_units() > 0 ? compute_units() : 256;
-    // Long runs per wave pay once the grid still fills the device (about 2 waves per SIMD).
-    const int cols = (t.cols == 0 ? chunks * slots / kRingColsWide >= 8 * cus : t.cols >= kRingColsWide)
-                         ? kRingColsWide : 1;
-    const int64_t per_block = (int64_t)kWaves * cols;
-    // A chunk without an aligned slot is all edge and shorter than two slots.
-    a.edge_blocks = (int32_t)((2 * (slot - 1) + kBlock - 1) / kBlock);
-    const int64_t bpc = a.edge_blocks + (slots + per_block - 1) / per_block;
-    a.blocks_per_chunk = (int32_t)bpc;
-    const int64_t grid = bpc * chunks;
-    if (bpc > 0x7fffffffLL || grid > 0x7fffffffLL)
+    RingArgs g;
+    g.q = d / n;
+    g.r = d % n;
+    g.mean = mean;
+    g.reserved = 0;
+    StreamArgs a;
+    Shape sh;
+    (void)plan_range(a, sh, t, n, ld, v, 64 * (int64_t)v, lo, hi, hi);
+    // the ring kernel exists for 8, 4 and 1 loads per row and never splits the rows of a block
+    int cols = sh.cols >= kStageColsWide ? kStageColsWide
+             : sh.cols >= kStageColsNarrow ? kStageColsNarrow : 1;
+    sh.cols = cols;
+    sh.rowsplit = 0;
+    const int64_t slots = (a.hi_a - a.lo_a) / (64 * (int64_t)v);
+    const int stage = stage_tiles_for(t, sh, v, slots, n, out, nullptr);
+    if (stage > 0)                 // the burst kernels exist for the two large-range shapes only
+        cols = sh.cols == kStageColsNarrow ? kStageColsNarrow : kStageColsWide;
+    const int64_t per_block = (int64_t)kWaves * cols * (stage > 0 ? stage : 1);
+    const int64_t grid = (slots + per_block - 1) / per_block + a.edge_blocks;
+    if (grid <= 0)
+        return BRACE_OK;
+    if (grid > 0x7fffffffLL)
         return fail(BRACE_ERANGE, "range needs %lld blocks, more than one launch can hold",
                     (long long)grid);
-    hipLaunchKernelGGL(brace_ring_pick(v, cols), dim3((unsigned)grid), dim3(kBlock), 0, stream,
-                       updates, a, out);
+    ring_sum_kernel_t k = brace_ring_pick(v, cols, stage > 0);
+    size_t lds = 0;
+    if (stage > 0) {
+        const int rcs = allow_stage_lds(reinterpret_cast<const void*>(k));
+        if (rcs != BRACE_OK)
+            return rcs;
+        lds = kStageBytes;
+    }
+    hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(kBlock), lds, stream, updates, a, g, out, stage);
     return check_launch("ring-order sum kernel");
 }
 
@@ -1775,7 +1777,7 @@ int brace_rar_aggregate(const float* updates_dev, int64_t n, int64_t d,
         return rc;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (params->order == 1)
-        return launch_ring_sum(updates_dev, n, d, ld, params->mean, out_dev, 0, n, stream);
+        return launch_ring_sum(updates_dev, n, d, ld, params->mean, out_dev, 0, d, stream);
     return launch_sum(updates_dev, n, d, ld, scale, out_dev, 0, d, stream);
 }
 
@@ -1793,8 +1795,7 @@ int brace_rar_aggregate_chunk(const float* updates_dev, int64_t n, int64_t d, in
         return rc;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (params->order == 1)
-        return launch_ring_sum(updates_dev, n, d, ld, params->mean, out_dev, chunk, chunk + 1,
-                               stream);
+        return launch_ring_sum(updates_dev, n, d, ld, params->mean, out_dev, lo, hi, stream);
     return launch_sum(updates_dev, n, d, ld, scale, out_dev, lo, hi, stream);
 }
 
@@ -1862,6 +1863,8 @@ int brace_init_device(void)
                 if (rc == BRACE_OK)
                     rc = allow_stage_lds(
                         reinterpret_cast<const void*>(brace_sum_pick_staged(v, cols, pipe)));
+                if (rc == BRACE_OK)
+                    rc = allow_stage_lds(reinterpret_cast<const void*>(brace_ring_pick(v, cols, 1)));
                 if (rc != BRACE_OK)
                     return rc;
             }

@@ -228,7 +228,7 @@ struct SumOp {
 // One translation unit per (op, load width) instantiates its share of the kernels.
 brace_dev::stream_staged_kernel_t<brace_dev::VoteOp> brace_vote_pick_staged(int v, int cols, int pipe);
 brace_dev::stream_staged_kernel_t<brace_dev::SumOp> brace_sum_pick_staged(int v, int cols, int pipe);
-brace_dev::ring_sum_kernel_t brace_ring_pick(int v, int cols);
+brace_dev::ring_sum_kernel_t brace_ring_pick(int v, int cols, int staged);
 brace_dev::stream_kernel_t<brace_dev::VoteOp> brace_vote_pick_v1(int cols, int ru, int nt, int pipe,
                                                                  int rs);
 brace_dev::stream_kernel_t<brace_dev::VoteOp> brace_vote_pick_v2(int cols, int ru, int nt, int pipe,

@@ -441,18 +441,16 @@ stream_kernel_t<Op> pick_cols(int cols, int ru, int nt, int pipe, int rs)
 // starts as client c's own sub-vector and every following client adds its own to what it
 // received, so coordinate k of chunk c is ((g_c + g_{c+1}) + ...) + g_{c-1} (indices mod n)
 // in the clients' precision, one fp32 rounding per step.  The start row therefore depends on
-// the chunk, and a grid covers a run of chunks: every chunk gets the same number of blocks,
-// the first `edge_blocks` of them take the chunk's unaligned ends one coordinate per thread,
-// the rest its aligned body; a wave folds rows c .. n-1 and then 0 .. c-1.
+// the chunk a coordinate falls in.  The launch layout is that of the kernels above (aligned
+// body of wave slots, edges one coordinate per thread, optionally results parked in LDS and
+// written as one burst per block); a wave looks up the chunk of its run of slots, folds rows
+// c .. n-1 and then 0 .. c-1, and falls back to one slot at a time, and inside a slot that a
+// chunk boundary cuts to one coordinate at a time, where the run spans two chunks.
 // ---------------------------------------------------------------------------------------
 struct RingArgs {
-    int64_t ld;
-    int64_t q, r;           // chunk c is [c*q + min(c, r), + q + (c < r))
-    int32_t n;
+    int64_t q, r;           // chunk c is [c*q + min(c, r), + q + (c < r)): the first r hold q + 1
     int32_t mean;           // 1: divide the sum by n once, in fp32 (Mean rule of Sec. 2.1)
-    int32_t chunk0;         // first chunk of the run
-    int32_t blocks_per_chunk;
-    int32_t edge_blocks;    // per chunk
+    int32_t reserved;
 };
 
 struct RingSumOp {
@@ -462,85 +460,226 @@ struct RingSumOp {
     __device__ static __forceinline__ void add(State& s, float v) { s.acc += v; }
 };
 
-__device__ __forceinline__ float ring_result(float acc, const RingArgs& a)
+__device__ __forceinline__ int ring_chunk_of(int64_t k, const RingArgs& g)
 {
-    return a.mean ? __fdiv_rn(acc, (float)a.n) : acc;
+    const int64_t head = g.r * (g.q + 1);       // coordinates held by the longer chunks
+    return (int)(k < head ? k / (g.q + 1) : g.r + (k - head) / g.q);   // k >= head implies q >= 1
 }
 
+__device__ __forceinline__ float ring_result(float acc, int n, const RingArgs& g)
+{
+    return g.mean ? __fdiv_rn(acc, (float)n) : acc;
+}
+
+// One coordinate, rows in the ring order of its chunk.
+__device__ __forceinline__ float ring_one(const float* __restrict__ updates, int64_t ld, int n,
+                                          int64_t k, const RingArgs& g)
+{
+    const int c = ring_chunk_of(k, g);
+    float acc = updates[(int64_t)c * ld + k];
+    for (int i = c + 1; i < n; ++i)
+        acc += updates[(int64_t)i * ld + k];
+    for (int i = 0; i < c; ++i)
+        acc += updates[(int64_t)i * ld + k];
+    return ring_result(acc, n, g);
+}
+
+// One wave folds all n rows in the ring order of chunk c (rows c, c+1, ..., n-1, 0, ..., c-1)
+// for COLS adjacent slots from wave-uniform coordinate k0: the double-buffered batches of
+// stream_fold, with the row of a batch entry looked up by its position in that sequence, so
+// that the wrap from row n-1 to row 0 does not drain the loads in flight.
 template <int V, int COLS, int RU>
-__device__ __forceinline__ void ring_slots(const float* __restrict__ updates, const RingArgs& a,
-                                           int c, int64_t k0, int lane, float* __restrict__ out)
+__device__ __forceinline__ void ring_fold(const float* __restrict__ updates, int64_t ld, int n,
+                                          int c, int64_t k0, int lane,
+                                          RingSumOp::State (&st)[COLS][V])
 {
     typedef typename Vec<V>::type VT;
-    RingSumOp::State st[COLS][V];
+    const float* col = updates + k0;            // wave-uniform
+    const uint32_t loff = (uint32_t)lane * V;
+    int j = 0;                                  // position in the sequence of the next row to request
+    auto row_of = [&](int pos) {
+        const int r = c + pos;
+        return col + (int64_t)(r >= n ? r - n : r) * ld;
+    };
+    auto load_batch = [&](VT (&x)[RU][COLS]) {
 #pragma unroll
-    for (int s = 0; s < COLS; ++s)
+        for (int r = 0; r < RU; ++r) {
+            const float* row = row_of(j + r);
 #pragma unroll
-        for (int e = 0; e < V; ++e)
-            RingSumOp::init(st[s][e]);
-    stream_fold<RingSumOp, V, COLS, RU, true, true>(updates + (int64_t)c * a.ld, a.ld, a.n - c, k0,
-                                                    lane, st);
-    stream_fold<RingSumOp, V, COLS, RU, true, true>(updates, a.ld, c, k0, lane, st);
+            for (int s = 0; s < COLS; ++s)
+                x[r][s] = load_vec<V, true>(row + loff + s * (64 * V));
+        }
+        j += RU;
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto fold = [&](const VT (&x)[RU][COLS]) {
 #pragma unroll
-    for (int s = 0; s < COLS; ++s) {
-        VT o;
+        for (int r = 0; r < RU; ++r)
 #pragma unroll
-        for (int e = 0; e < V; ++e)
-            set_elem<V>(o, e, ring_result(st[s][e].acc, a));
-        store_vec<true>(reinterpret_cast<VT*>(out + k0 + s * (64 * V) + (int64_t)lane * V), o);
+            for (int s = 0; s < COLS; ++s)
+#pragma unroll
+                for (int e = 0; e < V; ++e)
+                    RingSumOp::add(st[s][e], elem<V>(x[r][s], e));
+    };
+    if (n >= RU) {
+        VT xa[RU][COLS], xb[RU][COLS];
+        load_batch(xa);
+        while (j + 2 * RU <= n) {
+            load_batch(xb);
+            fold(xa);
+            load_batch(xa);
+            fold(xb);
+        }
+        if (j + RU <= n) {
+            load_batch(xb);
+            fold(xa);
+            fold(xb);
+        } else {
+            fold(xa);
+        }
+    }
+    for (; j < n; ++j) {                        // the last n mod RU rows
+        const float* row = row_of(j);
+        VT x[COLS];
+#pragma unroll
+        for (int s = 0; s < COLS; ++s)
+            x[s] = load_vec<V, true>(row + loff + s * (64 * V));
+#pragma unroll
+        for (int s = 0; s < COLS; ++s)
+#pragma unroll
+            for (int e = 0; e < V; ++e)
+                RingSumOp::add(st[s][e], elem<V>(x[s], e));
     }
 }
 
-template <int V, int COLS, int RU>
-__global__ void __launch_bounds__(kBlock)
-ring_sum_kernel(const float* __restrict__ updates, const RingArgs a, float* __restrict__ out)
+// COLS slots from wave-uniform coordinate k0; emit(slot, values) receives the lane's V results
+// of slot `slot` (0 .. COLS-1) of the run.
+template <int V, int COLS, int RU, class Emit>
+__device__ __forceinline__ void ring_slots(const float* __restrict__ updates, int64_t ld, int n,
+                                           const RingArgs& g, int64_t k0, int lane, Emit emit)
 {
-    const int c = a.chunk0 + (int)(blockIdx.x / (unsigned)a.blocks_per_chunk);   // block-uniform
-    const int t = (int)(blockIdx.x % (unsigned)a.blocks_per_chunk);
-    const int64_t lo = (int64_t)c * a.q + (c < a.r ? c : a.r);
-    const int64_t hi = lo + a.q + (c < a.r ? 1 : 0);
     constexpr int64_t kSlot = 64 * V;
-    int64_t lo_a = (lo + kSlot - 1) / kSlot * kSlot;
-    int64_t hi_a = hi / kSlot * kSlot;
-    if (lo_a >= hi_a)
-        lo_a = hi_a = lo;                      // no body: the whole chunk is edge
-    if (t < a.edge_blocks) {
-        const int64_t e = (int64_t)t * kBlock + threadIdx.x;
-        const int64_t head = lo_a - lo;
-        const int64_t k = (e < head) ? lo + e : hi_a + (e - head);
-        if (k >= hi)
-            return;
-        float acc = updates[(int64_t)c * a.ld + k];
-        for (int i = c + 1; i < a.n; ++i)
-            acc += updates[(int64_t)i * a.ld + k];
-        for (int i = 0; i < c; ++i)
-            acc += updates[(int64_t)i * a.ld + k];
-        out[k] = ring_result(acc, a);
+    const int c_first = ring_chunk_of(k0, g);                               // wave-uniform
+    const int c_last = ring_chunk_of(k0 + COLS * kSlot - 1, g);
+    if (c_first == c_last) {
+        RingSumOp::State st[COLS][V];
+#pragma unroll
+        for (int s = 0; s < COLS; ++s)
+#pragma unroll
+            for (int e = 0; e < V; ++e)
+                RingSumOp::init(st[s][e]);
+        ring_fold<V, COLS, RU>(updates, ld, n, c_first, k0, lane, st);
+#pragma unroll
+        for (int s = 0; s < COLS; ++s) {
+            float v[V];
+#pragma unroll
+            for (int e = 0; e < V; ++e)
+                v[e] = ring_result(st[s][e].acc, n, g);
+            emit(s, v);
+        }
         return;
     }
+    if constexpr (COLS > 1) {
+        for (int s = 0; s < COLS; ++s)              // a chunk boundary inside the run: slot by slot
+            ring_slots<V, 1, RU>(updates, ld, n, g, k0 + s * kSlot, lane,
+                                 [&](int, const float (&v)[V]) { emit(s, v); });
+    } else {
+        float v[V];                                 // a chunk boundary inside the slot
+#pragma unroll
+        for (int e = 0; e < V; ++e)
+            v[e] = ring_one(updates, ld, n, k0 + (int64_t)lane * V + e, g);
+        emit(0, v);
+    }
+}
+
+template <int V, int COLS, int RU, bool STAGED>
+__global__ void __launch_bounds__(kBlock)
+ring_sum_kernel(const float* __restrict__ updates, const StreamArgs a, const RingArgs g,
+                float* __restrict__ out, const int stage_tiles)
+{
+    typedef typename Vec<V>::type VT;
+    if ((int64_t)blockIdx.x < a.edge_blocks) {
+        const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+        const int64_t head = a.lo_a - a.lo;
+        const int64_t k = (e < head) ? a.lo + e : a.hi_a + (e - head);
+        if (k < a.hi)
+            out[k] = ring_one(updates, a.ld, a.n, k, g);
+        return;
+    }
+    const int64_t b = (int64_t)blockIdx.x - a.edge_blocks;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int64_t slots = (hi_a - lo_a) / kSlot;
-    const int64_t s0 = ((int64_t)(t - a.edge_blocks) * kWaves + wave) * COLS;
-    if (s0 >= slots)
-        return;
-    if (s0 + COLS <= slots) {
-        ring_slots<V, COLS, RU>(updates, a, c, lo_a + s0 * kSlot, lane, out);
+    constexpr int64_t kSlot = 64 * V;
+    const int64_t slots = (a.hi_a - a.lo_a) / kSlot;
+    if constexpr (!STAGED) {
+        const int64_t s0 = (b * kWaves + wave) * COLS;
+        if (s0 >= slots)
+            return;
+        const int64_t k0 = a.lo_a + s0 * kSlot;
+        auto store = [&](int64_t kbase) {
+            return [=](int s, const float (&v)[V]) {
+                VT o;
+#pragma unroll
+                for (int e = 0; e < V; ++e)
+                    set_elem<V>(o, e, v[e]);
+                store_vec<true>(reinterpret_cast<VT*>(out + kbase + s * kSlot + (int64_t)lane * V), o);
+            };
+        };
+        if (s0 + COLS <= slots) {
+            ring_slots<V, COLS, RU>(updates, a.ld, a.n, g, k0, lane, store(k0));
+        } else {
+            for (int64_t s = s0; s < slots; ++s)       // fewer than COLS slots left at the very end
+                ring_slots<V, 1, RU>(updates, a.ld, a.n, g, a.lo_a + s * kSlot, lane,
+                                     store(a.lo_a + s * kSlot));
+        }
     } else {
-        for (int64_t s = s0; s < slots; ++s)       // fewer than COLS slots left at the chunk's end
-            ring_slots<V, 1, RU>(updates, a, c, lo_a + s * kSlot, lane, out);
+        extern __shared__ unsigned char lds_raw[];
+        float* stage = reinterpret_cast<float*>(lds_raw);
+        constexpr int64_t kTileSlots = (int64_t)kWaves * COLS;
+        const int64_t slot0 = b * stage_tiles * kTileSlots;         // first slot of this block's group
+        auto park = [&](int64_t sbase) {
+            return [=](int s, const float (&v)[V]) {
+#pragma unroll
+                for (int e = 0; e < V; ++e)
+                    stage[(sbase - slot0 + s) * kSlot + lane * V + e] = v[e];
+            };
+        };
+        for (int t = 0; t < stage_tiles; ++t) {
+            const int64_t s0 = slot0 + (t * kTileSlots + (int64_t)wave * COLS);
+            if (s0 >= slots)
+                break;                                              // wave-uniform; the barrier is below
+            if (s0 + COLS <= slots) {
+                ring_slots<V, COLS, RU>(updates, a.ld, a.n, g, a.lo_a + s0 * kSlot, lane, park(s0));
+            } else {
+                for (int64_t s = s0; s < slots; ++s)
+                    ring_slots<V, 1, RU>(updates, a.ld, a.n, g, a.lo_a + s * kSlot, lane, park(s));
+            }
+        }
+        __syncthreads();
+        const int64_t base = a.lo_a + slot0 * kSlot;
+        int64_t valid = (int64_t)stage_tiles * kTileSlots * kSlot;
+        if (valid > a.hi_a - base)
+            valid = a.hi_a - base;                                  // a multiple of kSlot, hence of 4
+        for (int64_t i = (int64_t)threadIdx.x * 4; i < valid; i += kBlock * 4)
+            __builtin_nontemporal_store(*reinterpret_cast<const f32x4*>(stage + i),
+                                        reinterpret_cast<f32x4*>(out + base + i));
     }
 }
 
-using ring_sum_kernel_t = void (*)(const float*, const RingArgs, float*);
+using ring_sum_kernel_t = void (*)(const float*, const StreamArgs, const RingArgs, float*, int);
 
-constexpr int kRingColsWide = 8;
-
-// Long chunks: 8 loads per row, 2 rows per batch; short ones: one load per row, 4 rows.
+// Tile shapes of the ring-order kernel: the two large-range shapes (also staged) and one load
+// per row for short ranges.
 template <int V>
-ring_sum_kernel_t pick_ring(int cols)
+ring_sum_kernel_t pick_ring(int cols, bool staged)
 {
-    return cols == kRingColsWide ? ring_sum_kernel<V, kRingColsWide, 2> : ring_sum_kernel<V, 1, 4>;
+    if (cols >= kStageColsWide)
+        return staged ? ring_sum_kernel<V, kStageColsWide, kStageUnroll, true>
+                      : ring_sum_kernel<V, kStageColsWide, kStageUnroll, false>;
+    if (cols >= kStageColsNarrow)
+        return staged ? ring_sum_kernel<V, kStageColsNarrow, kStageUnroll, true>
+                      : ring_sum_kernel<V, kStageColsNarrow, kStageUnroll, false>;
+    return ring_sum_kernel<V, 1, 4, false>;
 }
 
 }  // namespace brace_dev

@@ -9,11 +9,11 @@ brace_dev::stream_kernel_t<brace_dev::SumOp> brace_sum_pick_v1(int cols, int ru,
 
 // The ring-order fp32 sum for every load width lives here too: this translation unit has
 // the fewest other kernels.
-brace_dev::ring_sum_kernel_t brace_ring_pick(int v, int cols)
+brace_dev::ring_sum_kernel_t brace_ring_pick(int v, int cols, int staged)
 {
     switch (v) {
-    case 4: return brace_dev::pick_ring<4>(cols);
-    case 2: return brace_dev::pick_ring<2>(cols);
-    default: return brace_dev::pick_ring<1>(cols);
+    case 4: return brace_dev::pick_ring<4>(cols, staged != 0);
+    case 2: return brace_dev::pick_ring<2>(cols, staged != 0);
+    default: return brace_dev::pick_ring<1>(cols, false);
     }
 }

@@ -133,12 +133,42 @@ def test_ring_order_load_widths_and_tile_shapes_agree():
     want = O.rar_sum_ring_order(upd.cpu().numpy())
     try:
         for vec in (0, 1, 2, 4):
-            for cols in (0, 1, 8):
-                B.brace_set_tuning(vec=vec, cols=cols)
-                out = torch.empty(d, device=DEV, dtype=torch.float32)
-                B.brace_rar_aggregate(upd, out, order=1)
-                torch.cuda.synchronize()
-                assert bits_equal(out.cpu().numpy(), want), (vec, cols)
+            for cols in (0, 1, 2, 4, 8):
+                for stage in (0, 1, 2):
+                    B.brace_set_tuning(vec=vec, cols=cols, stage_writes=stage)
+                    out = torch.empty(d, device=DEV, dtype=torch.float32)
+                    B.brace_rar_aggregate(upd, out, order=1)
+                    torch.cuda.synchronize()
+                    assert bits_equal(out.cpu().numpy(), want), (vec, cols, stage)
+    finally:
+        B.brace_reset_tuning()
+
+
+@pytest.mark.parametrize("n,d,ld,offset", [(3, 64, None, 0), (5, 257, None, 0), (7, 8192, None, 0),
+                                           (7, 8193, None, 0), (10, 40_000, None, 0),
+                                           (33, 70_001, None, 0), (8, 50_000, 50_002, 0),
+                                           (8, 50_000, 50_001, 0), (9, 123_456, None, 2),
+                                           (20, 300_007, None, 0), (100, 250_000, None, 0),
+                                           (300, 70_000, None, 0)])
+def test_ring_order_staged_bursts_forced(n, d, ld, offset):
+    # The burst-writing variant forced on small and ragged inputs: many chunk boundaries fall
+    # inside a wave's run of slots and inside single slots (300 clients x 70,000: chunks of 233).
+    upd = device_matrix(n, d, seed=n * 3 + d, ld=ld, offset=offset)
+    want = O.rar_sum_ring_order(upd.cpu().numpy())
+    try:
+        B.brace_set_tuning(stage_writes=2)
+        guard = torch.full((d + 64,), 3.0, device=DEV, dtype=torch.float32)
+        out = guard[32: 32 + d]
+        B.brace_rar_aggregate(upd, out, order=1)
+        torch.cuda.synchronize()
+        g = guard.cpu().numpy()
+        assert bits_equal(g[32: 32 + d], want)
+        assert (g[:32] == 3.0).all() and (g[32 + d:] == 3.0).all()
+        parts = torch.full((d,), 7.0, device=DEV, dtype=torch.float32)
+        for c in range(n):
+            B.brace_rar_aggregate(upd, parts, chunk=c, order=1)
+        torch.cuda.synchronize()
+        assert bits_equal(parts.cpu().numpy(), want)
     finally:
         B.brace_reset_tuning()
 
