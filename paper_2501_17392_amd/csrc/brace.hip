@@ -707,7 +707,7 @@ int stage_tiles_for(const brace_tuning_t& t, const Shape& sh, int v, int64_t slo
 }
 
 // Opt a kernel in to more than the default 64 KiB of dynamic LDS (once per kernel and device).
-int allow_stage_lds(const void* kernel)
+int allow_stage_lds(const void* kernel, size_t bytes = kStageBytes)
 {
     struct Seen { const void* kernel; int dev; };
     static Seen done[64] = {};
@@ -722,11 +722,10 @@ int allow_stage_lds(const void* kernel)
         if (s.kernel == kernel && s.dev == dev)
             return BRACE_OK;
     const hipError_t err = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                               (int)kStageBytes);
+                                               (int)bytes);
     if (err != hipSuccess) {
         (void)hipGetLastError();
-        return fail(BRACE_EHIP, "cannot reserve %zu bytes of LDS: %s", kStageBytes,
-                    hipGetErrorString(err));
+        return fail(BRACE_EHIP, "cannot reserve %zu bytes of LDS: %s", bytes, hipGetErrorString(err));
     }
     for (Seen& s : done)
         if (!s.kernel) {           // a full table only means the attribute is set again next time
@@ -1394,21 +1393,61 @@ int quantize_to_planes(const PlaneForm& form, const float* updates_dev, int64_t 
     if (rc != BRACE_OK)
         return rc;
 
-    const int spans_per_burst = form.two_planes ? kQuantGroup : kVoteGroup;   // 128 KiB either way
     const int64_t spans_row = (d + kQuantSpan - 1) / kQuantSpan;
-    const int64_t groups = (spans_row + spans_per_burst - 1) / spans_per_burst;    // per row
     const brace_tuning_t t = current_tuning();
-    // The burst kernel runs one block per compute unit at a time (2 MiB of input each), so its
-    // blocks come in rounds and a thinly filled last round costs as much as a full one.
+    const int64_t cus = compute_units() > 0 ? compute_units() : 256;
+    // The burst kernels run one block per compute unit at a time (about 2 MiB of input each),
+    // so their blocks come in rounds and a thinly filled last round costs as much as a full one.
     // Measured: ahead by 2-5 % with well filled rounds (n = 64, d = 8 M: 4.0 rounds; n = 8,
     // d = 100 M: 5.97; n = 100, d = 25 M: 18.75), behind with ragged ones (n = 50, d = 11 M:
     // 4.3 rounds, 0.447 against 0.408 ms; n = 100, d = 8 M: 6.25 rounds, 601 against 572 us).
-    const int64_t cus = compute_units() > 0 ? compute_units() : 256;
-    const int64_t blocks = groups * n;
-    const double fill = (double)blocks / (double)((blocks + cus - 1) / cus * cus);
-    const bool staged = t.stage_writes == 2 ||
-                        (t.stage_writes == 0 && spans_row >= spans_per_burst && blocks >= 4 * cus &&
-                         fill >= 0.9);
+    auto round_fill = [&](int64_t spans_per_burst, int64_t* blocks_out) {
+        const int64_t blocks = (spans_row + spans_per_burst - 1) / spans_per_burst * n;
+        *blocks_out = blocks;
+        return (double)blocks / (double)((blocks + cus - 1) / cus * cus);
+    };
+    auto bursts_pay = [&](int64_t spans_per_burst, int64_t blocks, double fill) {
+        return t.stage_writes == 2 || (t.stage_writes == 0 && spans_row >= spans_per_burst &&
+                                       blocks >= 4 * cus && fill >= 0.9);
+    };
+    // Rows of whole 16-byte vectors take the 4-dword form, with bursts of 144 KiB unless the
+    // rounds of 128 KiB bursts are clearly fuller.
+    const bool wide_ok = aligned_to(updates_dev, 16) && ld % 4 == 0 && d % 4 == 0;
+    if (wide_ok) {
+        const int kib = form.two_planes ? 1 : 2;                // spans per KiB of burst
+        int64_t blocks_a, blocks_b;
+        const double fill_a = round_fill(kQuantWideGroup * kib, &blocks_a);
+        const double fill_b = round_fill(kQuantGroup * kib, &blocks_b);
+        const bool take_a = fill_a + 0.03 >= fill_b;
+        const int64_t group = (take_a ? kQuantWideGroup : kQuantGroup) * kib;
+        const int64_t blocks = take_a ? blocks_a : blocks_b;
+        if (bursts_pay(group, blocks, take_a ? fill_a : fill_b)) {
+            if (blocks > 0x7fffffffLL)
+                return fail(BRACE_ERANGE, "matrix too large for one launch");
+            const size_t lds = (size_t)group / kib * 1024;
+            const void* k = form.two_planes
+                                ? reinterpret_cast<const void*>(brace_quantize_wide_kernel<true>)
+                                : reinterpret_cast<const void*>(brace_quantize_wide_kernel<false>);
+            rc = allow_stage_lds(k, kQuantWideBytes);
+            if (rc != BRACE_OK)
+                return rc;
+            const int64_t groups = (spans_row + group - 1) / group;
+            if (form.two_planes)
+                hipLaunchKernelGGL(brace_quantize_wide_kernel<true>, dim3((unsigned)blocks),
+                                   dim3(kQuantBlock), lds, stream, updates_dev, ld, d, planes_dev,
+                                   ld_words, row_words, groups, (int)group, 0);
+            else
+                hipLaunchKernelGGL(brace_quantize_wide_kernel<false>, dim3((unsigned)blocks),
+                                   dim3(kQuantBlock), lds, stream, updates_dev, ld, d, planes_dev,
+                                   ld_words, row_words, groups, (int)group, up_if_not_negative);
+            return check_launch("wide quantize kernel");
+        }
+    }
+    const int spans_per_burst = form.two_planes ? kQuantGroup : kVoteGroup;   // 128 KiB either way
+    const int64_t groups = (spans_row + spans_per_burst - 1) / spans_per_burst;    // per row
+    int64_t blocks;
+    const double fill = round_fill(spans_per_burst, &blocks);
+    const bool staged = bursts_pay(spans_per_burst, blocks, fill);
     if (staged) {
         if (blocks > 0x7fffffffLL)
             return fail(BRACE_ERANGE, "matrix too large for one launch");
@@ -1871,6 +1910,12 @@ int brace_init_device(void)
     int rc = allow_stage_lds(reinterpret_cast<const void*>(brace_quantize_staged_kernel));
     if (rc == BRACE_OK)
         rc = allow_stage_lds(reinterpret_cast<const void*>(brace_quantize_1bit_staged_kernel));
+    if (rc == BRACE_OK)
+        rc = allow_stage_lds(reinterpret_cast<const void*>(brace_quantize_wide_kernel<true>),
+                             kQuantWideBytes);
+    if (rc == BRACE_OK)
+        rc = allow_stage_lds(reinterpret_cast<const void*>(brace_quantize_wide_kernel<false>),
+                             kQuantWideBytes);
     if (rc != BRACE_OK)
         return rc;
     uint32_t* ws = nullptr;

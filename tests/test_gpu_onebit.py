@@ -54,7 +54,11 @@ def to_device(g, ld=None, offset=0):
     (3, 4096, None, 0, 0), (3, 4097, None, 0, 0), (7, 12_345, None, 1, 4), (6, 20_000, 20_003, 2, 8),
     (10, 70_001, None, 0, 0),
     # rows longer than one 256-span burst (1,048,576 coordinates), ragged last burst and span
-    (3, 1_048_576, None, 0, 0), (2, 1_048_577, None, 3, 4), (3, 2_200_003, 2_200_005, 1, 8)])
+    (3, 1_048_576, None, 0, 0), (2, 1_048_577, None, 3, 4), (3, 2_200_003, 2_200_005, 1, 8),
+    # rows of whole 16-byte vectors (the 4-dword burst kernel when bursts are forced): ragged last
+    # span, last burst of one span, exactly one burst of 288 spans and one span more, padded pitch
+    (2, 4, None, 0, 0), (3, 4100, None, 0, 0), (5, 12_344, 12_348, 0, 4), (2, 1_179_648, None, 0, 0),
+    (2, 1_179_652, None, 4, 0), (3, 2_400_004, 2_400_008, 8, 8)])
 @pytest.mark.parametrize("stage", [0, 1, 2], ids=["auto", "per-span-stores", "bursts"])
 @pytest.mark.parametrize("zs", [1, -1])
 def test_one_bit_quantize_matches_oracle(n, d, ld, offset, extra, stage, zs):

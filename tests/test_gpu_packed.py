@@ -64,7 +64,11 @@ def planes_buffer(n, d, extra_words=0, pitched=False):
     (4, 64, None, 0, 0), (5, 1000, None, 0, 0), (3, 4095, None, 0, 0), (3, 4096, None, 0, 0),
     (3, 4097, None, 0, 0), (7, 12_345, None, 1, 4), (6, 20_000, 20_003, 2, 8), (10, 70_001, None, 0, 0),
     # rows longer than one 128-span burst (524,288 coordinates), ragged last burst and last span
-    (3, 524_288, None, 0, 0), (2, 524_289, None, 3, 4), (3, 1_100_003, 1_100_005, 1, 8)])
+    (3, 524_288, None, 0, 0), (2, 524_289, None, 3, 4), (3, 1_100_003, 1_100_005, 1, 8),
+    # rows of whole 16-byte vectors (the 4-dword burst kernel when bursts are forced): ragged last
+    # span, last burst of one span, exactly one burst of 144 spans and one span more, padded pitch
+    (2, 4, None, 0, 0), (3, 4100, None, 0, 0), (5, 12_344, 12_348, 0, 4), (2, 589_824, None, 0, 0),
+    (2, 589_828, None, 4, 0), (3, 1_200_004, 1_200_008, 8, 8)])
 @pytest.mark.parametrize("stage", [0, 1, 2], ids=["auto", "per-span-stores", "bursts"])
 def test_quantize_matches_oracle_planes(n, d, ld, offset, extra, stage):
     g = special(n, d, seed=n * 11 + d)
