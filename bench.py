@@ -32,9 +32,19 @@ HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published peak
 # names the summary that holds it.  A workload without a counter run reports null.
 PROFILED_TRAFFIC = {
     "cfg3_n100_d25M_lie": {
-        "bytes": 10_003_433_600,
-        "source": "profiles/stream_kernel_VoteOp_cfg3_n100_d25M.md (FETCH 10,000,307,000 B + "
-                  "WRITE 3,126,600 B per launch)",
+        "bytes": 10_003_554_406,
+        "source": "profiles/stream_kernel_VoteOp_cfg3_n100_d25M.md (FETCH 10,000,427,213 B + "
+                  "WRITE 3,127,194 B per launch; algorithmic 10,003,125,000 B)",
+    },
+    "cfg4_n64_d100M_sparse_mix": {
+        "bytes": 25_612_905_984,
+        "source": "profiles/stream_kernel_VoteOp_cfg2_cfg4.md (algorithmic 25,612,500,000 B)",
+    },
+    "cfg2_n50_d11173962_inversion": {
+        "bytes": 2_298_414_080,
+        "source": "profiles/stream_kernel_VoteOp_cfg2_cfg4.md (algorithmic 2,236,189,148 B; rows "
+                  "are 8 mod 128 bytes apart, so the lines at the ends of every wave's run are "
+                  "fetched twice)",
     },
 }
 
@@ -153,6 +163,9 @@ def bench_large(B, synth, w, lam, steps, stream, dev, check_cols):
         "vote_kernel_ms": vote_ms,
         "vote_kernel_GBps": vote_bytes / (vote_ms * 1e-3) / 1e9,
         "vote_kernel_frac": vote_bytes / (vote_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "vote_kernel_traffic": (PROFILED_TRAFFIC.get(w.name) or {}).get("bytes"),
+        "vote_kernel_traffic_source": (PROFILED_TRAFFIC.get(w.name) or {}).get(
+            "source", "no counter run for this workload"),
         "gpu_matches_oracle_on_sample": match,
         "oracle_sample": f"first and last {min(check_cols, w.d)} coordinates x all clients",
         "generate_s": gen_s,
@@ -401,6 +414,9 @@ def main():
              nd4 + 8 * w.d + 2 * wb),
             ("update_direct", lambda: B.brace_aggregate_update(upd, w.f, model, 1e-3, args.lam,
                                                                stream=stream), nd4 + 8 * w.d),
+            ("update_noalloc", lambda: B.brace_aggregate_update_noalloc(upd, w.f, model, 1e-3,
+                                                                        args.lam, stream=stream),
+             nd4 + 8 * w.d + 2 * wb),
             ("quantize", lambda: B.brace_quantize(upd, signs, stream=stream), nd4 + 4 * w.n * rw),
             ("vote_packed", lambda: B.brace_vote_packed(signs, w.d, w.f, args.lam, out=other,
                                                         stream=stream),
