@@ -76,6 +76,18 @@ def time_on_stream(fn, reps, stream, warm=2):
     return ev[0].elapsed_time(ev[reps]) / reps, each
 
 
+def warm_for(fn, seconds):
+    """Untimed calls for at least `seconds`: after a stretch with the GPU idle (the CPU oracle
+    leg, the launch-bound small workloads) a 0.3 ms kernel runs several per cent slow until
+    the clocks are back up, which takes longer than a fixed handful of calls."""
+    import torch
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(10):
+            fn()
+        torch.cuda.synchronize()
+
+
 def sample_windows(d, cols):
     """Column windows the oracle is run on: the first `cols` coordinates and the last ones
     (the ragged end of the vector), merged when they touch."""
@@ -144,10 +156,9 @@ def bench_large(B, synth, w, lam, steps, stream, dev, check_cols):
     gen_s = time.perf_counter() - t0
     out = torch.empty(w.d, device=dev, dtype=torch.float32)
     bits = torch.empty((w.d + 31) // 32, device=dev, dtype=torch.int32)
-    # ten untimed calls first: right after the generator's many small kernels the first launches
-    # of a 0.3 ms kernel run several per cent slow
+    warm_for(lambda: B.brace_aggregate(upd, w.f, lam, out=out, stream=stream), 0.1)
     step_ms, each = time_on_stream(
-        lambda: B.brace_aggregate(upd, w.f, lam, out=out, stream=stream), steps, stream, warm=10)
+        lambda: B.brace_aggregate(upd, w.f, lam, out=out, stream=stream), steps, stream)
     match = oracle_matches(upd, lam, out, sample_windows(w.d, check_cols))
     vote_ms, _ = time_on_stream(
         lambda: B.brace_aggregate(upd, w.f, lam, out=None, out_bits=bits, stream=stream),
