@@ -129,3 +129,63 @@ def test_planes_route_in_a_graph_after_init_device():
         ref = O.rar_sum_direct(host)
         got = total.cpu().numpy().astype(np.float64)
         assert np.all(np.abs(got - ref) <= 1e-6 + 1e-5 * np.abs(ref)), replay
+
+
+def test_noalloc_update_ring_order_and_wide_quantize_in_a_graph():
+    """The allocation-free fused update (its bit-words live in the library's own workspace, whose
+    address brace_init_device looks up ahead of the capture), the ring-order fp32 sum and the
+    4-dword burst quantize, captured without warm-up launches and replayed with new inputs."""
+    assert torch.cuda.is_available()
+    B.lib()
+    B.brace_reset_tuning()
+    n, d, lam, eta = 12, 144 * 4096 + 8192 + 4, 1.0, 0.25        # rows of whole 16-byte vectors
+    upd = torch.empty(n, d, device=DEV)
+    fill(upd, 3)
+    w = torch.zeros(d, device=DEV)
+    total = torch.zeros(d, device=DEV)
+    rw, rp = B.brace_packed_row_words(d), B.brace_packed_row_pitch(d)
+    signs = torch.zeros(n, rp, device=DEV, dtype=torch.int32)[:, :rw]
+    vw, vp = B.brace_1bit_row_words(d), B.brace_1bit_row_pitch(d)
+    votes = torch.zeros(n, vp, device=DEV, dtype=torch.int32)[:, :vw]
+    out = torch.zeros(d, device=DEV)
+
+    B.brace_init_device()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    try:
+        B.brace_set_tuning(split_writes=2, stage_writes=2)
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                B.brace_aggregate_update_noalloc(upd, 0, w, eta, lam)
+                B.brace_rar_aggregate(upd, total, order=1)
+                B.brace_quantize(upd, signs)
+                B.brace_quantize_1bit(upd, -1, votes)
+                B.brace_vote_1bit(votes, d, 0, lam, out=out)
+    finally:
+        B.brace_reset_tuning()
+    torch.cuda.synchronize()
+
+    model = np.zeros(d, dtype=np.float32)
+    for replay in range(3):
+        fill(upd, 300 + replay)
+        out.fill_(7.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        host = upd.cpu().numpy()
+        want = O.brace_direct(host, lam)
+        model = O.model_update(model, want.out, np.float32(eta)).astype(np.float32)
+        assert np.array_equal(w.cpu().numpy(), model), replay          # +-0.25 steps are exact in fp32
+        ring = O.rar_sum_ring_order(host)
+        assert np.array_equal(total.cpu().numpy().view(np.uint32), ring.view(np.uint32)), replay
+        assert np.array_equal(signs.cpu().numpy().view(np.uint32), O.sign_planes(host)), replay
+        assert np.array_equal(votes.cpu().numpy().view(np.uint32), O.vote_plane(host, -1)), replay
+        assert np.array_equal(out.cpu().numpy(), O.brace_direct(host, lam, -1).out), replay
+        # the same entry point called eagerly in between gives the same model
+        w2 = torch.from_numpy(model).to(DEV)
+        w3 = w2.clone()
+        B.brace_aggregate_update_noalloc(upd, 0, w2, eta, lam)
+        B.brace_aggregate_update(upd, 0, w3, eta, lam)
+        torch.cuda.synchronize()
+        assert torch.equal(w2, w3)
