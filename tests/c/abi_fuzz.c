@@ -35,6 +35,11 @@ int main(void)
         brace_params_t p;
         brace_params_init(&p);
         p.lambda = lams[rnd() % (sizeof lams / sizeof *lams)];
+        if (n > 0 && (rnd() % 3) == 0) {        /* the saturation corners of the threshold, relative to n */
+            const float corners[] = {(float)n, (float)n - 0.5f, (float)n - 1.0f, -(float)n - 1.0f,
+                                     -(float)n - 0.5f, -(float)n, -(float)n + 0.5f};
+            p.lambda = corners[rnd() % (sizeof corners / sizeof *corners)];
+        }
         p.zero_sign = (int)(rnd() % 3) - 1;
         p.rule = (rnd() % 8) == 0;
         p.ld = (rnd() % 3) ? 0 : (d >= 0 && d < INT64_MAX - 2000 ? d + pad : d);
