@@ -175,6 +175,71 @@ def test_sum_mean_random_case(seed):
     assert untouched(whole, d, 7.0, out_off), tag
 
 
+@pytest.mark.parametrize("seed", range(60))
+def test_ring_order_sum_random_case(seed):
+    """order = 1: bit-exact against the oracle's fp32 ring, whole vector or one chunk, any tuning."""
+    rng = np.random.default_rng(2500 + seed)
+    n, d, ld, offset = random_shape(rng)
+    g = (rng.standard_normal((n, d)) * 10.0 ** rng.integers(-3, 4, size=(n, 1))).astype(np.float32)
+    g[rng.random((n, d)) < 0.05] = 0.0
+    upd = device_matrix(g, ld, offset)
+    mean = bool(rng.integers(0, 2))
+    tuning = random_tuning(rng)
+    out_off = int(rng.choice([0, 0, 1, 2, 4]))
+    whole, out = guarded(d, 7.0, torch.float32, out_off)
+    chunk = int(rng.integers(0, n)) if rng.integers(0, 2) else None
+    lo, hi = (0, d) if chunk is None else O.chunk_range(n, d, chunk)
+    tag = dict(seed=seed, n=n, d=d, ld=ld, offset=offset, mean=mean, chunk=chunk, **tuning)
+    print(tag, flush=True)
+    try:
+        B.brace_set_tuning(**tuning)
+        B.brace_rar_aggregate(upd, out, mean=mean, chunk=chunk, order=1)
+    finally:
+        B.brace_reset_tuning()
+    torch.cuda.synchronize()
+    want = O.mean_ring_order(g) if mean else O.rar_sum_ring_order(g)
+    got = out.cpu().numpy()
+    assert np.array_equal(got[lo:hi].view(np.uint32), want[lo:hi].view(np.uint32)), tag
+    assert (got[:lo] == 7.0).all() and (got[hi:] == 7.0).all(), tag
+    assert untouched(whole, d, 7.0, out_off), tag
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_noalloc_update_random_case(seed):
+    """The allocation-free fused update against the oracle and, bit for bit, against
+    brace_aggregate_update with a bit array, under any tuning."""
+    rng = np.random.default_rng(3500 + seed)
+    n, d, ld, offset = random_shape(rng)
+    g = votes_matrix(rng, n, d)
+    upd = device_matrix(g, ld, offset)
+    lam = float(rng.choice([-1, 0, 1, 2, 5]))
+    eta = float(rng.choice([1e-3, 0.01, 0.25, 0.5]))
+    zs = int(rng.choice([0, 1, -1]))
+    tuning = random_tuning(rng)
+    w0 = rng.standard_normal(d).astype(np.float32)
+    w_off = int(rng.choice([0, 0, 1, 2, 4]))
+    whole, w = guarded(d, 5.0, torch.float32, w_off)
+    w.copy_(torch.from_numpy(w0))
+    ref = torch.from_numpy(w0).to(DEV)
+    bits = torch.zeros(((d + 31) // 32,), device=DEV, dtype=torch.int32)
+    tag = dict(seed=seed, n=n, d=d, ld=ld, offset=offset, lam=lam, eta=eta, zs=zs, **tuning)
+    print(tag, flush=True)
+    try:
+        B.brace_set_tuning(**tuning)
+        B.brace_aggregate_update_noalloc(upd, 0, w, eta, lam, zs)
+        B.brace_aggregate_update(upd, 0, ref, eta, lam, zs, out_bits=bits)
+    finally:
+        B.brace_reset_tuning()
+    torch.cuda.synchronize()
+    agg = O.brace_direct(g, lam, zs).out
+    want = O.model_update(w0, agg, np.float32(eta))
+    got = w.cpu().numpy()
+    diff = np.abs(got.astype(np.float64) - want)
+    assert np.all(diff <= np.spacing(np.abs(want).astype(np.float32)).astype(np.float64)), tag
+    assert np.array_equal(got, ref.cpu().numpy()), tag
+    assert untouched(whole, d, 5.0, w_off), tag
+
+
 @pytest.mark.parametrize("seed", range(80))
 def test_update_random_case(seed):
     rng = np.random.default_rng(3000 + seed)
