@@ -28,7 +28,8 @@ int brace_set_pointer_checks(int32_t enabled);
  */
 typedef struct brace_tuning {
     uint32_t struct_size;  /* sizeof(brace_tuning_t)                                             */
-    int32_t  vec;          /* widest load in dwords: 0 = auto (what alignment allows), 1, 2, 4    */
+    int32_t  vec;          /* widest load in dwords: 1, 2, 4 (narrowed to what alignment allows);  */
+                           /* 0 = auto: what alignment allows, 2 instead of 4 for large ranges     */
     int32_t  cols;         /* loads per lane per row: 1, 2, 4 or 8; 0 = from the size of the range */
     int32_t  unroll;       /* rows per batch of loads: 2, 4 or 8; 0 = from the size of the range  */
     int32_t  nontemporal;  /* 1: streaming (non-temporal) loads                                   */

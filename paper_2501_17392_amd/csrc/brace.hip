@@ -538,6 +538,23 @@ int pick_width(const float* updates, int64_t n, int64_t ld, const void* out4, co
     return v;
 }
 
+// Large ranges run about 1 % (n = 100) to 8 % (n = 200) faster with 2-dword than with 4-dword
+// loads even where the rows would allow the wider ones: half the registers per wave, twice the
+// waves per compute unit and tiles of half the size, which fill the last round of blocks
+// better (n = 100, d = 25 M: 1.418 against 1.431 ms; n = 64, d = 100 M: 3.663 against 3.688 ms;
+// n = 50, d = 11.2 M with rows on whole lines: 0.316 against 0.340 ms).  Not so where the
+// floats written are a large share of the traffic (n = 8, d = 100 M: 0.68 against 0.57 ms), for
+// ranges that fit the memory-side cache or a single ring chunk (n = 100, d = 500 k: 0.033
+// against 0.030 ms), or when sign-sums leave through per-lane stores.  `few` is the client
+// count below which the call's float traffic outweighs the gain.
+int narrow_if_large(int v, const brace_tuning_t& t, int64_t n, int64_t coords, int64_t few,
+                    bool per_lane_sums)
+{
+    if (v == 4 && t.vec == 0 && !per_lane_sums && n >= few && 4 * n * coords >= kSplitMinBytes)
+        return 2;
+    return v;
+}
+
 // Tile shape of one launch: loads per lane per row, rows per batch, row split.
 struct Shape {
     int cols, unroll, rowsplit;
@@ -797,6 +814,9 @@ int launch_vote(const float* updates, int64_t n, int64_t d, int64_t ld, int thre
     if (w)
         v = pick_width(updates, n, ld, w, nullptr, v);
     uint32_t* bits = static_cast<uint32_t*>(p->out_bits_dev);
+    // the in-place update without a bit-word carrier reads and writes the model in the stream
+    v = narrow_if_large(v, t, n, hi - lo, (w && !bits && !ws_bits) ? kNarrowBelowClients : kStageBelowClients,
+                        p->sums_dev != nullptr);
 
     // Split the writes off the read stream?  Needs float output, 16-byte aligned, and whole
     // 1024-coordinate groups; worth it only for large ranges unless forced.
@@ -915,7 +935,8 @@ int launch_sum(const float* updates, int64_t n, int64_t d, int64_t ld, double sc
     if (rc != BRACE_OK)
         return rc;
     const brace_tuning_t t = current_tuning();
-    const int v = pick_width(updates, n, ld, out, nullptr, t.vec);
+    const int v = narrow_if_large(pick_width(updates, n, ld, out, nullptr, t.vec), t, n, hi - lo,
+                                  kStageBelowClients, false);
     SumOp op;
     op.out = out;
     op.scale = scale;
@@ -967,7 +988,8 @@ int launch_ring_sum(const float* updates, int64_t n, int64_t d, int64_t ld, int 
     if (rc != BRACE_OK)
         return rc;
     const brace_tuning_t t = current_tuning();
-    const int v = pick_width(updates, n, ld, out, nullptr, t.vec);
+    const int v = narrow_if_large(pick_width(updates, n, ld, out, nullptr, t.vec), t, n, hi - lo,
+                                  kStageBelowClients, false);
     RingArgs g;
     g.q = d / n;
     g.r = d % n;
