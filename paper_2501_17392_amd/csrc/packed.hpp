@@ -141,8 +141,8 @@ brace_quantize_staged_kernel(const float* __restrict__ updates, int64_t ld, int6
 // consecutive coordinates, its two compares per value give a nibble per plane, and three
 // butterfly steps over 8 neighbouring lanes assemble the 32-bit words; the lane that leads each
 // group of 8 writes the word (pair) straight into its final place in the block's LDS stage, so
-// the burst at the end is a plain copy.  A third of the vector instructions of the ballot
-// form and 16 KiB in flight per wave.  Measured at n = 100, d = 25 M (both planes): 1.69 ms
+// the burst at the end is a plain copy.  Half the vector instructions of the ballot form
+// (7.5 against 16 lane operations per value) and 16 KiB in flight per wave.  Measured at n = 100, d = 25 M (both planes): 1.69 ms
 // with bursts of 144 KiB, 1.72 ms with 128 KiB, against 1.77 ms for the ballot form with
 // 128 KiB bursts and 1.40 ms for the reads alone.
 // TWO: both planes (x > 0, x < 0), else the one-bit vote (up_if_not_negative as in vote_span).
