@@ -362,7 +362,8 @@ def main():
             "traffic": traffic["bytes"] if traffic else None,
             "traffic_source": traffic["source"] if traffic else
             "no counter run for this workload",
-            "kernel": "brace_dev::stream_kernel<VoteOp, ...> (the streaming vote kernel)",
+            "kernel": "brace_dev::stream_kernel<VoteOp, V, COLS, RU, NT, PIPE, RS> (the streaming vote "
+                      "kernel; <VoteOp, 2, 8, 2, true, true, false> on the headline workload)",
             "measured_on": f"{K} launches of the kernel alone (bit output) right after the timed "
                            "steps, same launch shape as inside a step",
             "algorithmic_bytes_per_launch": vote_bytes,
