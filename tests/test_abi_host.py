@@ -44,6 +44,21 @@ def test_library_exports_every_declared_symbol(L):
     assert set(B.EXPORTS) <= set(declared)
 
 
+def test_method_header_holds_no_process_wide_state_calls():
+    # include/brace.h is the method; tuning, the pointer-check switch and the probes are
+    # process-wide state and measurement aids and live in include/brace_tuning.h.
+    inc = os.path.join(ROOT, "include")
+    method = re.sub(r"/\*.*?\*/", "", open(os.path.join(inc, "brace.h")).read(), flags=re.S)
+    tuning = re.sub(r"/\*.*?\*/", "", open(os.path.join(inc, "brace_tuning.h")).read(), flags=re.S)
+    for name in ("brace_set_tuning", "brace_get_tuning", "brace_probe_read", "brace_probe_copy",
+                 "brace_set_pointer_checks", "brace_tuning_t"):
+        assert name not in method, name
+        assert name in tuning, name
+    for name in ("brace_aggregate", "brace_aggregate_chunk", "brace_chunk_range", "brace_threshold",
+                 "brace_rar_aggregate", "brace_aggregate_update_noalloc"):
+        assert re.search(r"\b%s\s*\(" % name, method), name
+
+
 def test_header_is_plain_c_and_host_entry_points_work_from_c(L, tmp_path):
     # gcc -std=c99 -pedantic on the header, a C program linked against the library, no GPU call.
     import subprocess
