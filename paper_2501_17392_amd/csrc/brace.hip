@@ -1578,11 +1578,13 @@ int vote_on_planes(const PlaneForm& form, const uint32_t* planes_dev, int64_t n,
     if (hi_a > lo_a) {
         const int64_t d_body = hi_a - lo_a;
         const int64_t cols4 = whole ? form.row_words(d) / 4 : d_body / form.coords_per_load;
-        // A wave walks `seq` neighbouring 64-column groups one after the other: up to 3 while
-        // that still leaves about 6 waves for every compute unit.
+        // A wave walks `seq` neighbouring 64-column groups one after the other: up to 3, so
+        // that about 7 waves remain for every compute unit (6,104 groups: 3 per wave, 97 us
+        // against 102 us with 1 and 100 us with 4; 3,052 groups: 2 per wave, 49.7 us against
+        // 51.2 us with 1 and 54.4 us with 3).
         const int64_t groups64 = (cols4 + 63) / 64;
         const int64_t cus = compute_units() > 0 ? compute_units() : 256;
-        const int64_t fit = groups64 / (6 * cus);
+        const int64_t fit = (2 * groups64 + 7 * cus) / (14 * cus);      // groups / (7 cus), rounded
         const int seq = fit >= 3 ? 3 : fit >= 1 ? (int)fit : 1;
         const int64_t grid = (groups64 + (int64_t)kWaves * seq - 1) / ((int64_t)kWaves * seq);
         if (grid > 0x7fffffffLL)
